@@ -1,0 +1,204 @@
+/*
+ * kvm.h - C ABI of libkvm: paged-KV-cache migration for one MI355X (gfx950).
+ *
+ * The library implements the data path of Mell's adaptive request migration
+ * (arXiv 2501.06709, Sec. "Adaptive Request Migration", step "Hybrid
+ * Migration": the class of requests that is moved as KV cache rather than as
+ * tokens).  A request's KV cache lives in a paged block pool (Sec. "Background
+ * & Related Work": KV cache in non-contiguous paged memory); migrating it means
+ * reading tokens [0,k) of every layer, K and V, through the source block table
+ * and writing them into freshly allocated blocks of another pool under a new
+ * block table.  Tokens [k,len) are the part the method would re-prefill from
+ * token ids on the destination and are never touched here.
+ *
+ * Conventions for every entry point
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HBM
+ *     addresses valid on the current HIP device.  The caller owns every buffer.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Kernels are
+ *     enqueued on it and the call returns without synchronising.  The library
+ *     allocates no device memory.
+ *   - Return value: KVM_OK (0) or a negative kvm_status.  All argument checks
+ *     run on the host before the first launch, so KVM_EINVAL / KVM_ENOMEM mean
+ *     that no device byte was written.  kvm_last_error() gives the detail.
+ *   - Elements are 16-bit (fp16 or bf16) and are moved as raw bit patterns.
+ */
+#ifndef KVM_H
+#define KVM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVM_OK = 0,
+  KVM_EINVAL = -1, /* bad argument: see kvm_last_error() */
+  KVM_ENOMEM = -2, /* free list cannot supply the blocks; nothing was popped */
+  KVM_EHIP = -3    /* a HIP call failed; kvm_last_error() holds its text */
+} kvm_status;
+
+typedef enum { KVM_F16 = 0, KVM_BF16 = 1 } kvm_dtype;
+
+/*
+ * Per-model KV layout (the method serves several models from one cluster, so a
+ * layout travels with every pool).  An element (layer l, kv in {0:K,1:V},
+ * physical block b, KV head h, slot s in [0,block_tokens), dim d) sits at
+ *   base + 2 * (l*stride_layer + kv*stride_kv + b*stride_block
+ *               + h*stride_head + s*stride_slot + d)          bytes.
+ * Strides are in elements, the dim stride is 1.  The same block id addresses
+ * the block in every (layer, kv) plane.  Required: head_dim*2 and every
+ * stride*2 are multiples of 16 bytes; n_q_heads is a multiple of n_kv_heads.
+ */
+typedef struct {
+  int32_t n_layers;
+  int32_t n_kv_heads;
+  int32_t n_q_heads;
+  int32_t head_dim;
+  int32_t block_tokens;
+  int32_t dtype; /* kvm_dtype */
+  int64_t stride_layer;
+  int64_t stride_kv;
+  int64_t stride_block;
+  int64_t stride_head;
+  int64_t stride_slot;
+} kvm_layout;
+
+/* One block pool: `base` is a device pointer, 16-byte aligned, caller-owned. */
+typedef struct {
+  void* base;
+  int64_t n_blocks;
+  kvm_layout layout;
+} kvm_pool;
+
+/*
+ * A batch of requests of ONE model with their block tables in CSR form.
+ * Request r owns table entries bt_offsets[r] .. bt_offsets[r+1]-1; entry j
+ * holds the physical block of tokens [j*B, j*B+B), B = block_tokens.
+ * k[r] is the split point of the method's migrate-versus-recompute choice:
+ * tokens [0,k[r]) are moved (or, for kvm_paged_decode, attended over);
+ * 0 <= k[r] <= B * (entries of r).  k[r] = 0 makes the request a no-op.
+ */
+typedef struct {
+  int32_t n_req;
+  const int32_t* bt_offsets;     /* host,   [n_req+1], bt_offsets[0] = 0 */
+  const int32_t* bt_blocks_dev;  /* device, [bt_offsets[n_req]] */
+  const int32_t* bt_blocks_host; /* host copy of bt_blocks_dev, or NULL.  When
+                                    given, every id that will be dereferenced is
+                                    range-checked, and on the writing side
+                                    checked for duplicates.  NULL skips those
+                                    checks: ids are then the caller's promise. */
+  const int32_t* k;              /* host,   [n_req] */
+} kvm_batch;
+
+/* ---- closed-form sizes (host, pure) -------------------------------------
+ * Sec. "System Model": a request's KV size grows linearly with its tokens;
+ * bytes per token = n_layers * 2 * n_kv_heads * head_dim * 2.  Return -1 on a
+ * NULL or inconsistent layout. */
+int64_t kvm_bytes_per_token(const kvm_layout* layout);
+int64_t kvm_block_bytes(const kvm_layout* layout); /* block_tokens * bytes_per_token */
+/* Sum over the batch of k[r] * bytes_per_token: the size of the staging buffer
+ * written by kvm_pack and read by kvm_unpack.  Exactly linear in k, no padding. */
+int64_t kvm_staging_bytes(const kvm_layout* layout, const kvm_batch* batch);
+
+/* Fill `out` with the canonical dense layout
+ *   pool[layer][kv][block][head][slot][dim]
+ * for a pool of n_blocks blocks.  Returns KVM_EINVAL on non-positive sizes,
+ * n_q_heads not a multiple of n_kv_heads, or head_dim*2 not a multiple of 16. */
+int kvm_layout_canonical(kvm_layout* out, int32_t n_layers, int32_t n_kv_heads,
+                         int32_t n_q_heads, int32_t head_dim, int32_t block_tokens,
+                         int32_t dtype, int64_t n_blocks);
+/* Bytes a pool with this layout and n_blocks spans from `base` (largest byte
+ * offset of any element + 1); -1 on a bad layout. */
+int64_t kvm_pool_span_bytes(const kvm_layout* layout, int64_t n_blocks);
+
+/* ---- the migration data path --------------------------------------------
+ * Sec. "Adaptive Request Migration" (KV-cache class of "Hybrid Migration") and
+ * Sec. "Motivation", Finding 4 (copying the KV of the legacy tokens relies on
+ * the cache being append-only, so a prefix [0,k) is a valid unit of transfer).
+ *
+ * Staging ("wire") format, shared by kvm_pack and kvm_unpack: requests in
+ * batch order, each as [layer][kv][head][token t < k[r]][dim], 16-bit elements,
+ * no padding; request r starts at byte (sum_{r'<r} k[r']) * bytes_per_token.
+ */
+
+/* Gather: staging[...] = src pool contents of tokens [0,k[r]) of each request.
+ * staging_dev: device, 16-byte aligned, staging_bytes >= kvm_staging_bytes().
+ * Reads the pool and the table only; writes exactly kvm_staging_bytes() bytes.
+ * KVM_EINVAL: NULL pointer, bad layout, k out of range, block id outside
+ * [0,n_blocks) (when host ids are given), staging too small or misaligned. */
+int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
+             int64_t staging_bytes, void* hip_stream);
+
+/* Scatter: inverse of kvm_pack into the blocks named by dst_reqs.  Slots
+ * >= k[r] mod B of a request's last block, and all other blocks of the pool,
+ * keep their bytes.  In addition to kvm_pack's checks: a block id that occurs
+ * twice among the written entries of dst_reqs is KVM_EINVAL. */
+int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* dst,
+               const kvm_batch* dst_reqs, void* hip_stream);
+
+/* Fused gather+scatter without staging: for every request r, layer, K and V,
+ * head and token t < k[r], the element at logical position t of the source
+ * request is copied to logical position t of the destination request.
+ * The source pool is never written (Sec. "Adaptive Request Migration",
+ * "Boundary Profiling": source memory stays allocated until the transfer is
+ * complete; releasing it is the caller's later step).
+ * KVM_EINVAL additionally when: n_req or any k[r] differs between the two
+ * batches; the layouts differ in anything but strides; src and dst are the
+ * same allocation region and a written dst block id is also a read src id. */
+int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* dst,
+                const kvm_batch* dst_reqs, void* hip_stream);
+
+/* ---- paged decode attention ----------------------------------------------
+ * Sec. "Background & Related Work": the decoding phase reads the KV cache of
+ * all previous tokens to produce the next one.  For request r, layer l, query
+ * head hq (KV head g = hq / (n_q_heads / n_kv_heads)):
+ *   s_t = scale * sum_d q[r][l][hq][d] * K_t[g][d],   t in [0,k[r])
+ *   out[r][l][hq][:] = sum_t softmax(s)_t * V_t[g][:]
+ * read through the block table.  q_dev: device, [n_req][n_layers][n_q_heads]
+ * [head_dim] in the pool's dtype.  out_dev: same shape, float32 when
+ * out_is_f32 != 0, else the pool's dtype (round to nearest even).  Accumulation
+ * is fp32.  scale = 0 selects 1/sqrt(head_dim).  A request with k[r] = 0 leaves
+ * its output rows untouched.
+ * workspace_dev / workspace_bytes: device scratch for splitting long contexts
+ * over several workgroups (size from kvm_decode_workspace_bytes; 16-byte
+ * aligned).  NULL or too small a workspace is legal: the context is then not
+ * split.  The result depends only on logical token positions, never on which
+ * physical blocks hold them. */
+int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev,
+                     void* out_dev, int out_is_f32, float scale, void* workspace_dev,
+                     int64_t workspace_bytes, void* hip_stream);
+int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs);
+
+/* ---- host free-list allocator (integers only) ----------------------------
+ * Destination blocks for a migrated request come from the destination pool's
+ * free list (capacity constraint of Sec. "System Model", Eq. 2).  Lowest free
+ * id first; all-or-nothing. */
+typedef struct kvm_freelist kvm_freelist;
+/* occupied: host, n_blocks bytes, non-zero = block in use; NULL = all free.
+ * Returns NULL on n_blocks <= 0 or n_blocks > 2^31-1. */
+kvm_freelist* kvm_freelist_create(int64_t n_blocks, const uint8_t* occupied);
+void kvm_freelist_destroy(kvm_freelist* fl);
+int64_t kvm_freelist_available(const kvm_freelist* fl);
+/* Pop the n lowest free ids into out_ids (host, ascending).  KVM_ENOMEM if
+ * fewer than n are free: then nothing is popped and out_ids is untouched. */
+int kvm_freelist_alloc(kvm_freelist* fl, int32_t n, int32_t* out_ids);
+/* Return ids to the list.  KVM_EINVAL (and no change) if an id is out of
+ * range, already free, or repeated in `ids`. */
+int kvm_freelist_free(kvm_freelist* fl, int32_t n, const int32_t* ids);
+
+/* ---- diagnostics ---------------------------------------------------------- */
+const char* kvm_strerror(int status);
+/* Detail of the last failure on the calling thread ("" if none); the pointer
+ * stays valid until the next failing call on this thread. */
+const char* kvm_last_error(void);
+/* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
+ * value gives KVM_EINVAL.  Names: "copy.unroll" (1,2,4,8 16-byte vectors per
+ * lane per workgroup pass), "copy.nontemporal" (0/1), "decode.max_splits"
+ * (1..64).  Process-wide; not thread-safe against concurrent launches. */
+int kvm_set_option(const char* name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVM_H */

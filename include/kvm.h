@@ -194,8 +194,10 @@ const char* kvm_strerror(int status);
 const char* kvm_last_error(void);
 /* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
  * value gives KVM_EINVAL.  Names: "copy.unroll" (1,2,4,8 16-byte vectors per
- * lane per workgroup pass), "copy.nontemporal" (0/1), "decode.max_splits"
- * (1..64).  Process-wide; not thread-safe against concurrent launches. */
+ * lane per workgroup pass), "copy.nontemporal" (0/1), "copy.plane_major" (0/1:
+ * workgroup order, plane or block outermost), "decode.max_splits" (1..64),
+ * "decode.force_splits" (0 = automatic, else exactly this many context splits).
+ * Process-wide; not thread-safe against concurrent launches. */
 int kvm_set_option(const char* name, int64_t value);
 
 #ifdef __cplusplus

@@ -35,7 +35,7 @@ _M2 = np.uint32(0x846CA68B)
 _GOLD = 0x9E3779B9
 _BLK = 0x85EBCA6B
 _YX = np.uint32(0x68E31DA4)
-INV_SD = np.float32(1.0 / 209.0239)
+INV_SD = np.float32(float.fromhex("0x1.398896p-8"))  # float32(1 / 209.0239)
 
 STREAM_SRC = 1
 STREAM_DST = 2

@@ -1,0 +1,98 @@
+// Device side of the synthetic input generator: fills a block pool (or part of
+// it) with the same counter-based values the numpy generator produces, so the
+// host can regenerate any block of a 100+ GiB pool without downloading it.
+// Input generation only: nothing of the migration path lives here.
+//
+// Element (plane p = layer*2+kv, block b, w = (head*B + slot)*D + dim):
+//   key = mix32(seed ^ mix32(stream * 0x9E3779B9 + p + 1))      (host, per plane)
+//   kb  = mix32(key + b * 0x85EBCA6B)
+//   x   = mix32(kb + w);  y = mix32(x ^ 0x68E31DA4)
+//   n   = (sum of the 8 bytes of x and y) - 1020
+//   val = round_to_nearest_even_16bit(float(n) * 0x1.398896p-8f)
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+static __host__ __device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7feb352du;
+  x ^= x >> 15;
+  x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+
+__device__ inline uint32_t byte_sum(uint32_t v) {
+  return (v & 0xff) + ((v >> 8) & 0xff) + ((v >> 16) & 0xff) + (v >> 24);
+}
+
+__device__ inline uint16_t gen16(uint32_t kb, uint32_t w, int bf16) {
+  const uint32_t x = mix32(kb + w);
+  const uint32_t y = mix32(x ^ 0x68E31DA4u);
+  const float f = (float)((int)(byte_sum(x) + byte_sum(y)) - 1020) * 0x1.398896p-8f /* float32(1/209.0239) */;
+  if (bf16) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+  return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+struct FillArgs {
+  char* base;
+  int64_t stride_layer, stride_kv, stride_block;  // bytes
+  uint32_t stride_head, stride_slot;              // bytes
+  int32_t H, B, D;
+  int32_t b0;      // first block to fill
+  int32_t bf16;
+  uint32_t seed, stream;
+};
+
+// grid: x = 8-element vectors of one (plane, block) / 256, y = block - b0, z = plane
+__global__ __launch_bounds__(256) void fill_kernel(const FillArgs a) {
+  const uint32_t plane = blockIdx.z;
+  const uint32_t b = a.b0 + blockIdx.y;
+  const uint32_t dv = a.D / 8;
+  const uint32_t vec = blockIdx.x * 256u + threadIdx.x;
+  if (vec >= (uint32_t)a.H * a.B * dv) return;
+  const uint32_t key = mix32(a.seed ^ mix32(a.stream * 0x9E3779B9u + plane + 1u));
+  const uint32_t kb = mix32(key + b * 0x85EBCA6Bu);
+  const uint32_t w0 = vec * 8u;
+  const uint32_t h = vec / (a.B * dv), rem = vec % (a.B * dv);
+  const uint32_t s = rem / dv, c = rem % dv;
+  uint32_t out[4];
+  for (int i = 0; i < 4; ++i)
+    out[i] = (uint32_t)gen16(kb, w0 + 2 * i, a.bf16) | ((uint32_t)gen16(kb, w0 + 2 * i + 1, a.bf16) << 16);
+  char* p = a.base + (int64_t)(plane >> 1) * a.stride_layer + (int64_t)(plane & 1) * a.stride_kv +
+            (int64_t)b * a.stride_block + (uint64_t)h * a.stride_head + (uint64_t)s * a.stride_slot +
+            c * 16u;
+  *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+// Fills blocks [b0, b1) of every (layer, kv) plane.  strides_bytes: layer, kv,
+// block, head, slot.  Returns the hipError_t of the launch as an int.
+extern "C" int kvmw_fill_pool(void* base_dev, const int64_t* strides_bytes, int L, int H, int D,
+                              int B, int bf16, int64_t b0, int64_t b1, uint32_t seed,
+                              uint32_t stream_id, void* hip_stream) {
+  if (!base_dev || !strides_bytes || D % 8 || b1 <= b0) return -1;
+  FillArgs a;
+  a.base = (char*)base_dev;
+  a.stride_layer = strides_bytes[0];
+  a.stride_kv = strides_bytes[1];
+  a.stride_block = strides_bytes[2];
+  a.stride_head = (uint32_t)strides_bytes[3];
+  a.stride_slot = (uint32_t)strides_bytes[4];
+  a.H = H; a.B = B; a.D = D;
+  a.bf16 = bf16;
+  a.seed = seed;
+  a.stream = stream_id;
+  const uint32_t vecs = (uint32_t)H * B * (D / 8);
+  for (int64_t b = b0; b < b1; b += 32768) {
+    const int64_t n = b1 - b < 32768 ? b1 - b : 32768;
+    a.b0 = (int32_t)b;
+    hipLaunchKernelGGL(fill_kernel, dim3((vecs + 255) / 256, (uint32_t)n, 2 * L), dim3(256), 0,
+                       (hipStream_t)hip_stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
+}

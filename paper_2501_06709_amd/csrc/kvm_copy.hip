@@ -1,0 +1,356 @@
+// Pack / unpack / fused migrate kernels for gfx950 and their C entry points.
+//
+// The data path of the KV-cache class of request migration (arXiv 2501.06709,
+// Sec. "Adaptive Request Migration", "Hybrid Migration"): tokens [0,k) of every
+// layer, K and V, are read through the source block table and written through
+// the destination block table (or to / from a contiguous staging buffer).
+//
+// All three operations are one kernel, `copy_kernel<MODE, U, NT>`:
+//  - a work item is (block entry of a request, plane = layer*2+kv, chunk); one
+//    256-lane workgroup moves up to U*256 16-byte vectors of it;
+//  - every lane issues its U loads before its first store, so a workgroup keeps
+//    U*4 KiB in flight; with 8 workgroups per CU that is 256 KiB per CU at U=8;
+//  - block ids and request descriptors are wave-uniform: they are read with
+//    scalar loads from the kernel-argument segment and the block table, which
+//    broadcasts them to all lanes without a vector load or LDS;
+//  - a full block of the dense layout is one contiguous run per plane
+//    (heads*block_tokens*head_dim*2 bytes) and is moved with no index math
+//    beyond base + lane*16; partial last blocks and other layouts go through a
+//    (head, slot, vector) decomposition of the lane's vector index.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "kvm_internal.h"
+
+namespace kvm {
+
+enum CopyMode { kMigrate = 0, kPack = 1, kUnpack = 2 };
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+struct PoolSide {
+  char* base;
+  const int32_t* bt;      // device block table (CSR payload)
+  int64_t stride_layer;   // bytes
+  int64_t stride_kv;
+  int64_t stride_block;
+  uint32_t stride_head;   // bytes, within a block
+  uint32_t stride_slot;
+  uint32_t dense;         // 1: a full block is one contiguous run per plane
+};
+
+struct CopyReq {
+  int32_t src_bt;      // first table entry of the request on the source side
+  int32_t dst_bt;      // ... on the destination side
+  int32_t k;           // tokens to move
+  int32_t first_item;  // index of the request's first block among the launch's items
+  int64_t stage_vec;   // staging offset of the request in 16-byte vectors
+};
+
+struct CopyArgs {
+  PoolSide src;        // pool side read by migrate / pack
+  PoolSide dst;        // pool side written by migrate / unpack
+  char* stage;         // staging buffer (pack writes, unpack reads)
+  int32_t n_req;
+  int32_t n_items;     // blocks holding tokens [0,k) over the launch's requests
+  int32_t n_planes;    // 2 * layers
+  int32_t n_chunks;    // workgroup passes per (item, plane)
+  int32_t H, B;
+  uint32_t DV;         // 16-byte vectors per token row (head_dim*2/16)
+  int32_t dv_shift;    // log2(DV) or -1
+  int32_t plane_major;
+  CopyReq req[kMaxReqPerLaunch];
+};
+
+__device__ __forceinline__ v4u load16(const char* p, bool nt) {
+  const v4u* q = reinterpret_cast<const v4u*>(p);
+  return nt ? __builtin_nontemporal_load(q) : *q;
+}
+__device__ __forceinline__ void store16(char* p, v4u v, bool nt) {
+  v4u* q = reinterpret_cast<v4u*>(p);
+  if (nt)
+    __builtin_nontemporal_store(v, q);
+  else
+    *q = v;
+}
+
+template <int MODE, int U, bool NT>
+__global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
+  // ---- decode the work item (all wave-uniform) ----
+  uint32_t wg = blockIdx.x;
+  const uint32_t chunk = wg % (uint32_t)a.n_chunks;
+  wg /= (uint32_t)a.n_chunks;
+  uint32_t item, plane;
+  if (a.plane_major) {
+    item = wg % (uint32_t)a.n_items;
+    plane = wg / (uint32_t)a.n_items;
+  } else {
+    plane = wg % (uint32_t)a.n_planes;
+    item = wg / (uint32_t)a.n_planes;
+  }
+  // request that owns the item: largest r with first_item[r] <= item
+  int r = 0;
+#pragma unroll
+  for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
+    const int t = r + s;
+    if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
+  }
+  const CopyReq rq = a.req[r];
+  const int32_t j = (int32_t)item - rq.first_item;  // logical block of the request
+  const int32_t rem_tokens = rq.k - j * a.B;
+  const uint32_t ns = rem_tokens < a.B ? (uint32_t)rem_tokens : (uint32_t)a.B;  // slots to move
+  const uint32_t layer = plane >> 1, kv = plane & 1;
+
+  const char* sbase = nullptr;
+  char* dbase = nullptr;
+  bool dense = ns == (uint32_t)a.B;
+  if (MODE != kUnpack) {
+    const int64_t blk = a.src.bt[rq.src_bt + j];
+    sbase = a.src.base + layer * a.src.stride_layer + kv * a.src.stride_kv + blk * a.src.stride_block;
+    dense = dense && a.src.dense;
+  }
+  if (MODE != kPack) {
+    const int64_t blk = a.dst.bt[rq.dst_bt + j];
+    dbase = a.dst.base + layer * a.dst.stride_layer + kv * a.dst.stride_kv + blk * a.dst.stride_block;
+    dense = dense && a.dst.dense;
+  }
+  const uint32_t per_head = ns * a.DV;          // vectors per head in this item
+  const uint32_t n_vec = per_head * (uint32_t)a.H;
+  const uint32_t v0 = chunk * (U * 256u) + threadIdx.x;
+  if (chunk * (U * 256u) >= n_vec) return;
+
+  // Lanes past the end of the item load its last vector again (always in
+  // bounds) and skip the store, so the loads stay unconditional straight-line code.
+  const uint32_t v_last = n_vec - 1;
+  v4u val[U];
+  if (MODE == kMigrate && dense) {
+    // one contiguous run on both sides
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t v = min(v0 + u * 256u, v_last);
+      val[u] = load16(sbase + (uint64_t)v * 16u, NT);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t v = v0 + u * 256u;
+      if (v < n_vec) store16(dbase + (uint64_t)v * 16u, val[u], NT);
+    }
+    return;
+  }
+
+  // general path: vector index -> (head, slot, vector-in-row)
+  char* stage_plane = nullptr;  // staging address of (request, plane, head 0, token j*B)
+  uint64_t stage_head = 0;      // bytes between heads in staging
+  if (MODE != kMigrate) {
+    stage_head = (uint64_t)rq.k * a.DV * 16u;
+    stage_plane = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)plane * a.H * rq.k * a.DV +
+                             (uint64_t)j * a.B * a.DV) * 16u;
+  }
+  uint32_t soff[U], doff[U];
+  uint64_t shead[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t v = min(v0 + u * 256u, v_last);
+    const uint32_t h = v / per_head;
+    const uint32_t w = v - h * per_head;  // slot*DV + dv
+    const uint32_t slot = a.dv_shift >= 0 ? (w >> a.dv_shift) : (w / a.DV);
+    const uint32_t dv = w - slot * a.DV;
+    soff[u] = h * a.src.stride_head + slot * a.src.stride_slot + dv * 16u;
+    doff[u] = h * a.dst.stride_head + slot * a.dst.stride_slot + dv * 16u;
+    shead[u] = (uint64_t)h * stage_head + (uint64_t)w * 16u;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    val[u] = load16(MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u], NT);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t v = v0 + u * 256u;
+    if (v < n_vec) store16(MODE == kPack ? stage_plane + shead[u] : dbase + doff[u], val[u], NT);
+  }
+}
+
+static int ilog2_exact(uint32_t v) {
+  if (!v || (v & (v - 1))) return -1;
+  int s = 0;
+  while ((1u << s) != v) ++s;
+  return s;
+}
+
+static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
+  PoolSide s;
+  const kvm_layout& l = p->layout;
+  s.base = (char*)p->base;
+  s.bt = b->bt_blocks_dev;
+  s.stride_layer = l.stride_layer * 2;
+  s.stride_kv = l.stride_kv * 2;
+  s.stride_block = l.stride_block * 2;
+  s.stride_head = (uint32_t)(l.stride_head * 2);
+  s.stride_slot = (uint32_t)(l.stride_slot * 2);
+  s.dense = l.stride_slot == l.head_dim && l.stride_head == (int64_t)l.block_tokens * l.head_dim;
+  return s;
+}
+
+template <int MODE>
+static hipError_t launch(const CopyArgs& a, uint32_t grid, hipStream_t stream) {
+  const Options& o = options();
+#define KVM_LAUNCH(U, NT) \
+  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), dim3(grid), dim3(256), 0, stream, a)
+  if (o.copy_nontemporal) {
+    switch (o.copy_unroll) {
+      case 1: KVM_LAUNCH(1, true); break;
+      case 2: KVM_LAUNCH(2, true); break;
+      case 4: KVM_LAUNCH(4, true); break;
+      default: KVM_LAUNCH(8, true); break;
+    }
+  } else {
+    switch (o.copy_unroll) {
+      case 1: KVM_LAUNCH(1, false); break;
+      case 2: KVM_LAUNCH(2, false); break;
+      case 4: KVM_LAUNCH(4, false); break;
+      default: KVM_LAUNCH(8, false); break;
+    }
+  }
+#undef KVM_LAUNCH
+  return hipGetLastError();
+}
+
+// Splits the batch into launches of at most kMaxReqPerLaunch requests and
+// enqueues them.  `sv` / `dv` are the validated views of the two sides (for
+// pack only `sv`, for unpack only `dv` is meaningful; the other aliases it).
+template <int MODE>
+static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& sv,
+                    const kvm_pool* dst, const kvm_batch* db, const BatchView& dv, char* stage,
+                    hipStream_t stream) {
+  const kvm_layout& l = (MODE == kUnpack ? dst : src)->layout;
+  const BatchView& view = MODE == kUnpack ? dv : sv;
+  CopyArgs a;
+  memset(&a, 0, sizeof a);
+  if (MODE != kUnpack) a.src = make_side(src, sb);
+  if (MODE != kPack) a.dst = make_side(dst, db);
+  if (MODE == kPack) a.dst = a.src;    // strides of the unused side are still
+  if (MODE == kUnpack) a.src = a.dst;  // read by the index math: keep them sane
+  a.stage = stage;
+  a.n_planes = 2 * l.n_layers;
+  a.H = l.n_kv_heads;
+  a.B = l.block_tokens;
+  a.DV = (uint32_t)(l.head_dim * 2 / 16);
+  a.dv_shift = ilog2_exact(a.DV);
+  a.plane_major = options().copy_plane_major;
+  const int U = options().copy_unroll;
+  const int64_t vec_per_item = (int64_t)l.n_kv_heads * l.block_tokens * a.DV;
+  a.n_chunks = (int32_t)ceil_div(vec_per_item, (int64_t)U * 256);
+  const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;  // vectors per token
+
+  int64_t stage_vec = 0;
+  int r = 0;
+  while (r < view.n_req) {
+    a.n_req = 0;
+    a.n_items = 0;
+    const int64_t max_items = (int64_t)0x7fffffff / ((int64_t)a.n_planes * a.n_chunks);
+    while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
+      if (view.nb[r] > max_items)
+        return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
+      if ((int64_t)a.n_items + view.nb[r] > max_items) break;
+      CopyReq& q = a.req[a.n_req++];
+      q.src_bt = sv.bt_off[r];
+      q.dst_bt = dv.bt_off[r];
+      q.k = view.k[r];
+      q.first_item = a.n_items;
+      q.stage_vec = stage_vec;
+      a.n_items += view.nb[r];
+      stage_vec += (int64_t)view.k[r] * bpt_vec;
+      ++r;
+    }
+    if (a.n_items == 0) continue;  // only k = 0 requests in this group
+    const uint32_t grid = (uint32_t)((int64_t)a.n_items * a.n_planes * a.n_chunks);
+    const hipError_t e = launch<MODE>(a, grid, stream);
+    if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
+  }
+  return KVM_OK;
+}
+
+static bool same_shape(const kvm_layout& a, const kvm_layout& b) {
+  return a.n_layers == b.n_layers && a.n_kv_heads == b.n_kv_heads && a.n_q_heads == b.n_q_heads &&
+         a.head_dim == b.head_dim && a.block_tokens == b.block_tokens && a.dtype == b.dtype;
+}
+
+}  // namespace kvm
+
+using namespace kvm;
+
+extern "C" {
+
+int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
+             int64_t staging_bytes, void* hip_stream) {
+  clear_error();
+  BatchView sv;
+  int rc = validate_side("kvm_pack: src", src, src_reqs, false, &sv);
+  if (rc) return rc;
+  const int64_t need = sv.total_tokens * kvm_bytes_per_token(&src->layout);
+  if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_pack: staging_dev is NULL");
+  if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_pack: staging_dev is not 16-byte aligned");
+  if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_pack: staging buffer too small");
+  return run_copy<kPack>(src, src_reqs, sv, src, src_reqs, sv, (char*)staging_dev,
+                         (hipStream_t)hip_stream);
+}
+
+int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* dst,
+               const kvm_batch* dst_reqs, void* hip_stream) {
+  clear_error();
+  BatchView dv;
+  int rc = validate_side("kvm_unpack: dst", dst, dst_reqs, true, &dv);
+  if (rc) return rc;
+  const int64_t need = dv.total_tokens * kvm_bytes_per_token(&dst->layout);
+  if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is NULL");
+  if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is not 16-byte aligned");
+  if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_unpack: staging buffer too small");
+  return run_copy<kUnpack>(dst, dst_reqs, dv, dst, dst_reqs, dv, (char*)staging_dev,
+                           (hipStream_t)hip_stream);
+}
+
+int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* dst,
+                const kvm_batch* dst_reqs, void* hip_stream) {
+  clear_error();
+  BatchView sv, dv;
+  int rc = validate_side("kvm_migrate: src", src, src_reqs, false, &sv);
+  if (rc) return rc;
+  rc = validate_side("kvm_migrate: dst", dst, dst_reqs, true, &dv);
+  if (rc) return rc;
+  if (!same_shape(src->layout, dst->layout))
+    return fail(KVM_EINVAL, "kvm_migrate: src and dst layouts differ in more than strides");
+  if (sv.n_req != dv.n_req) return fail(KVM_EINVAL, "kvm_migrate: n_req differs between src and dst");
+  for (int r = 0; r < sv.n_req; ++r)
+    if (sv.k[r] != dv.k[r]) return fail(KVM_EINVAL, "kvm_migrate: k differs between src and dst");
+  // Overlapping memory: only the same pool with disjoint block sets is allowed.
+  const char* s0 = (const char*)src->base;
+  const char* d0 = (const char*)dst->base;
+  const char* s1 = s0 + kvm_pool_span_bytes(&src->layout, src->n_blocks);
+  const char* d1 = d0 + kvm_pool_span_bytes(&dst->layout, dst->n_blocks);
+  if (s0 < d1 && d0 < s1) {
+    const kvm_layout &a = src->layout, &b = dst->layout;
+    const bool same = s0 == d0 && a.stride_layer == b.stride_layer && a.stride_kv == b.stride_kv &&
+                      a.stride_block == b.stride_block && a.stride_head == b.stride_head &&
+                      a.stride_slot == b.stride_slot && src->n_blocks == dst->n_blocks;
+    if (!same) return fail(KVM_EINVAL, "kvm_migrate: src and dst memory overlap but are not the same pool");
+    if (!src_reqs->bt_blocks_host || !dst_reqs->bt_blocks_host)
+      return fail(KVM_EINVAL, "kvm_migrate: in-pool migration needs host block ids on both sides");
+    std::vector<uint64_t> wr((size_t)ceil_div(dst->n_blocks, 64), 0);
+    for (int r = 0; r < dv.n_req; ++r)
+      for (int j = 0; j < dv.nb[r]; ++j) {
+        const int32_t id = dst_reqs->bt_blocks_host[dv.bt_off[r] + j];
+        wr[(size_t)id >> 6] |= 1ull << (id & 63);
+      }
+    for (int r = 0; r < sv.n_req; ++r)
+      for (int j = 0; j < sv.nb[r]; ++j) {
+        const int32_t id = src_reqs->bt_blocks_host[sv.bt_off[r] + j];
+        if (wr[(size_t)id >> 6] & (1ull << (id & 63)))
+          return fail(KVM_EINVAL, "kvm_migrate: a block is both read and written");
+      }
+  }
+  return run_copy<kMigrate>(src, src_reqs, sv, dst, dst_reqs, dv, nullptr, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,475 @@
+// Paged decode attention for gfx950 and its C entry point.
+//
+// The decoding phase reads the KV cache of all earlier tokens to produce the
+// next one (arXiv 2501.06709, Sec. "Background & Related Work").  Running it
+// over the destination pool after a migration shows that the moved cache is
+// usable.  One query token per (request, layer, query head):
+//   out = softmax(scale * q K^T) V  over tokens [0,k) read through the block table.
+//
+// The operation streams K and V once and does 1 (MHA) to 4 (grouped-query,
+// group 4) flops per byte, so it is bound by HBM and written for coalesced
+// 16-byte loads rather than for the matrix cores:
+//  - one 256-lane workgroup per (request, layer, KV head[, context split]); the
+//    G query heads that share the KV head are served from the same loads;
+//  - each of the 4 waves takes every 4th block of the range; within a wave a
+//    token row of D*2 bytes is spread over D/8 adjacent lanes (16 bytes each), so
+//    one load instruction covers 1 KiB of consecutive cache bytes;
+//  - q.K partial sums are reduced across those D/8 lanes with DPP lane
+//    permutes; every (wave, lane row) keeps its own online-softmax state
+//    (running max, sum, fp32 accumulator), merged through LDS at the end;
+//  - block ids are fetched 64 at a time, one per lane, and broadcast to the wave
+//    with readlane as the loop advances;
+//  - long contexts can be split over several workgroups whose partial states are
+//    merged by a second small kernel (log-sum-exp merge).
+// The order of every reduction depends on logical token positions only, so the
+// same logical cache in different physical blocks gives bit-identical output.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "kvm_internal.h"
+
+namespace kvm {
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no token seen yet"
+
+struct DecReq {
+  int32_t bt;   // first table entry of the request
+  int32_t k;    // context length
+  int32_t row;  // request index into q / out / workspace
+  int32_t pad;
+};
+
+struct DecArgs {
+  const char* base;
+  const int32_t* bt;
+  int64_t stride_layer;  // bytes
+  int64_t stride_kv;
+  int64_t stride_block;
+  uint32_t stride_head;
+  uint32_t stride_slot;
+  const uint16_t* q;
+  void* out;
+  float* ws;
+  int32_t L, H, Hq;
+  int32_t passes;       // query-head groups per KV head handled by separate workgroups
+  int32_t n_splits;
+  int32_t out_f32;
+  float scale_log2e;    // softmax scale * log2(e): scores live in the exp2 domain
+  DecReq req[kMaxReqPerLaunch];
+};
+
+__device__ __forceinline__ float dpp_xor1(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_xor2(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_half_mirror(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float dpp_mirror(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+}
+
+// Sum over groups of LPT adjacent lanes (LPT = 8 or 16); every lane of a group
+// ends with the group's total.  Steps: neighbours in a quad, then the other
+// quad of an 8-lane half (half mirror), then the other half of the 16-lane row.
+template <int LPT>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_xor1(v);
+  v += dpp_xor2(v);
+  v += dpp_half_mirror(v);
+  if (LPT == 16) v += dpp_mirror(v);
+  return v;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void widen8(v4u raw, float* f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (BF16) {
+      f[2 * i] = __builtin_bit_cast(float, raw[i] << 16);
+      f[2 * i + 1] = __builtin_bit_cast(float, raw[i] & 0xffff0000u);
+    } else {
+      typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+      const unsigned int w = raw[i];  // bit_cast needs a scalar object, not a vector element
+      const h2 h = __builtin_bit_cast(h2, w);
+      f[2 * i] = (float)h[0];
+      f[2 * i + 1] = (float)h[1];
+    }
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ uint16_t narrow(float f) {
+  if (BF16) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
+    return (uint16_t)(u >> 16);
+  }
+  return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// Workspace entry of one (request row, layer, query head, split): D unnormalised
+// accumulator values, then the running max (exp2 domain) and the running sum.
+__device__ __forceinline__ float* ws_entry(float* ws, const DecArgs& a, int row, int l, int hq,
+                                           int split, int D) {
+  return ws + ((((int64_t)row * a.L + l) * a.Hq + hq) * a.n_splits + split) * (D + 2);
+}
+
+template <int D, int B, int G, bool BF16>
+__global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
+  constexpr int LPT = D / 8;       // lanes per token row
+  constexpr int TPI = 64 / LPT;    // token rows per load instruction
+  constexpr int NI = B / TPI;      // load instructions per block and per K / V
+  constexpr int NP = 4 * TPI;      // online-softmax states per workgroup
+  static_assert(LPT == 8 || LPT == 16, "head_dim must be 64 or 128");
+  static_assert(B % TPI == 0, "block_tokens must be a multiple of the rows per load");
+
+  __shared__ float s_m[NP][G];
+  __shared__ float s_l[NP][G];
+  __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
+
+  const int pass = blockIdx.x % a.passes;
+  const int h = blockIdx.x / a.passes;
+  const int l = blockIdx.y;
+  const int r = blockIdx.z / a.n_splits;
+  const int split = blockIdx.z % a.n_splits;
+  const DecReq rq = a.req[r];
+  const int k = rq.k;
+  if (k <= 0) return;
+  const int nb = (k + B - 1) / B;
+  const int per = (nb + a.n_splits - 1) / a.n_splits;
+  const int jb = split * per;
+  const int je = min(nb, jb + per);
+  if (jb >= je) return;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int sub = lane % LPT;
+  const int row = lane / LPT;
+  const int hq0 = (h * a.passes + pass) * G;  // first query head served here
+
+  // query fragment: dims sub*8 .. sub*8+7 of each of the G heads, pre-scaled
+  float qf[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const uint16_t* qp = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0 + g) * D + sub * 8;
+    widen8<BF16>(*reinterpret_cast<const v4u*>(qp), qf[g]);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qf[g][c] *= a.scale_log2e;
+  }
+
+  float m[G], lsum[G], o[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = kNegBig;
+    lsum[g] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] = 0.f;
+  }
+
+  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head;
+  const char* vbase = kbase + a.stride_kv;
+  const uint32_t lane_off = (uint32_t)row * a.stride_slot + (uint32_t)sub * 16u;
+  const uint32_t inst_off = (uint32_t)TPI * a.stride_slot;
+
+  // this wave handles blocks jb + wave, jb + wave + 4, ...
+  const int n_it = (je - jb - wave + 3) / 4;  // may be <= 0
+  v4u kc[NI], vc[NI];
+  int ids = 0;
+  auto fetch_ids = [&](int it0) {
+    const int j = jb + wave + 4 * (it0 + lane);
+    ids = j < je ? a.bt[rq.bt + j] : 0;
+  };
+  auto load_block = [&](int it, v4u* kd, v4u* vd) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
+    const char* kp = kbase + blk * a.stride_block + lane_off;
+    const char* vp = vbase + blk * a.stride_block + lane_off;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      kd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * inst_off));
+      vd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp + i * inst_off));
+    }
+  };
+
+  if (n_it > 0) {
+    fetch_ids(0);
+    load_block(0, kc, vc);
+  }
+  for (int it = 0; it < n_it; ++it) {
+    v4u kn[NI], vn[NI];
+    const bool more = it + 1 < n_it;
+    if (more) {
+      if (((it + 1) & 63) == 0) fetch_ids(it + 1);
+      load_block(it + 1, kn, vn);
+    }
+    const int j = jb + wave + 4 * it;
+    const int t_limit = k - j * B;  // slots >= t_limit of this block are not context
+    if (t_limit < B) {
+      // Slots past the context may hold anything (NaN patterns included): clear
+      // their V rows so that a zero weight cannot turn them into NaN.
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        if (i * TPI + row >= t_limit) vc[i] = v4u{0u, 0u, 0u, 0u};
+    }
+
+    float s[NI][G];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float kf[8];
+      widen8<BF16>(kc[i], kf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float acc = qf[g][0] * kf[0];
+#pragma unroll
+        for (int c = 1; c < 8; ++c) acc = fmaf(qf[g][c], kf[c], acc);
+        s[i][g] = group_sum<LPT>(acc);
+      }
+    }
+    float p[NI][G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mx = m[g];
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        if (i * TPI + row < t_limit) mx = fmaxf(mx, s[i][g]);
+      const float alpha = __builtin_amdgcn_exp2f(m[g] - mx);
+      m[g] = mx;
+      float add = 0.f;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        p[i][g] = (i * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[i][g] - mx) : 0.f;
+        add += p[i][g];
+      }
+      lsum[g] = lsum[g] * alpha + add;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] *= alpha;
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      float vf[8];
+      widen8<BF16>(vc[i], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(p[i][g], vf[c], o[g][c]);
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        kc[i] = kn[i];
+        vc[i] = vn[i];
+      }
+    }
+  }
+
+  // ---- merge the NP states of the workgroup through LDS ----
+  const int slot = wave * TPI + row;
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    if (sub == 0) {
+      s_m[slot][g] = m[g];
+      s_l[slot][g] = lsum[g];
+    }
+    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
+    dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
+    dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int g = idx / D, d = idx % D;
+    float mx = kNegBig;
+#pragma unroll
+    for (int pidx = 0; pidx < NP; ++pidx) mx = fmaxf(mx, s_m[pidx][g]);
+    float acc = 0.f, den = 0.f;
+#pragma unroll
+    for (int pidx = 0; pidx < NP; ++pidx) {
+      const float wgt = __builtin_amdgcn_exp2f(s_m[pidx][g] - mx);
+      acc = fmaf(s_o[pidx][g][d], wgt, acc);
+      den = fmaf(s_l[pidx][g], wgt, den);
+    }
+    const int hq = hq0 + g;
+    if (a.n_splits == 1) {
+      const float res = acc / den;
+      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
+      if (a.out_f32)
+        reinterpret_cast<float*>(a.out)[oi] = res;
+      else
+        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
+    } else {
+      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
+      e[d] = acc;
+      if (d == 0) {
+        e[D] = mx;
+        e[D + 1] = den;
+      }
+    }
+  }
+}
+
+// Log-sum-exp merge of the context splits, in split order.
+template <int D, int B, bool BF16>
+__global__ __launch_bounds__(D) void merge_kernel(const DecArgs a) {
+  const int hq = blockIdx.x, l = blockIdx.y;
+  const DecReq rq = a.req[blockIdx.z];
+  if (rq.k <= 0) return;
+  const int nb = (rq.k + B - 1) / B;
+  const int per = (nb + a.n_splits - 1) / a.n_splits;
+  const int n_eff = (nb + per - 1) / per;  // splits that saw at least one block
+  const int d = threadIdx.x;
+  float mx = kNegBig;
+  for (int s = 0; s < n_eff; ++s) mx = fmaxf(mx, ws_entry(a.ws, a, rq.row, l, hq, s, D)[D]);
+  float acc = 0.f, den = 0.f;
+  for (int s = 0; s < n_eff; ++s) {
+    const float* e = ws_entry(a.ws, a, rq.row, l, hq, s, D);
+    const float wgt = __builtin_amdgcn_exp2f(e[D] - mx);
+    acc = fmaf(e[d], wgt, acc);
+    den = fmaf(e[D + 1], wgt, den);
+  }
+  const float res = acc / den;
+  const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
+  if (a.out_f32)
+    reinterpret_cast<float*>(a.out)[oi] = res;
+  else
+    reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
+}
+
+struct DecodePlan {
+  int g_tile;    // query heads per workgroup (1, 2 or 4)
+  int passes;    // workgroups per KV head
+  int n_splits;
+};
+
+static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
+  DecodePlan p;
+  const int G = l.n_q_heads / l.n_kv_heads;
+  p.g_tile = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
+  p.passes = G / p.g_tile;
+  const Options& o = options();
+  int s = 1;
+  if (o.decode_force_splits > 0) {
+    s = o.decode_force_splits;
+  } else {
+    // Fill 256 CUs (x4 resident workgroups) when the batch alone cannot, but
+    // keep at least 16 blocks (4 per wave) in every split.
+    const int64_t base = (int64_t)n_req * l.n_layers * l.n_kv_heads * p.passes;
+    const int64_t want = base > 0 ? ceil_div(2048, base) : 1;
+    const int64_t room = max_nb / 16;
+    s = (int)std::max<int64_t>(1, std::min<int64_t>(want, room));
+    s = std::min(s, o.decode_max_splits);
+  }
+  p.n_splits = std::max(1, std::min(s, 64));
+  return p;
+}
+
+static int64_t ws_bytes_for(const kvm_layout& l, int n_req, int n_splits) {
+  return (int64_t)n_req * l.n_layers * l.n_q_heads * n_splits * (l.head_dim + 2) * 4;
+}
+
+template <int D, int B, bool BF16>
+static hipError_t launch_decode(const DecArgs& a, const DecodePlan& p, int n_req, hipStream_t st) {
+  const dim3 grid(a.H * p.passes, a.L, n_req * p.n_splits);
+  switch (p.g_tile) {
+    case 4: hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_kernel<D, B, 1, BF16>), grid, dim3(256), 0, st, a); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || p.n_splits == 1) return e;
+  hipLaunchKernelGGL((merge_kernel<D, B, BF16>), dim3(a.Hq, a.L, n_req), dim3(D), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace kvm
+
+using namespace kvm;
+
+extern "C" {
+
+int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs) {
+  if (!layout_ok(layout, nullptr) || !reqs || reqs->n_req < 0 || (reqs->n_req > 0 && !reqs->k))
+    return -1;
+  int max_nb = 0;
+  for (int r = 0; r < reqs->n_req; ++r)
+    max_nb = std::max<int64_t>(max_nb, ceil_div(std::max(reqs->k[r], 0), layout->block_tokens));
+  const DecodePlan p = plan_decode(*layout, reqs->n_req, max_nb);
+  return p.n_splits > 1 ? ws_bytes_for(*layout, reqs->n_req, p.n_splits) : 0;
+}
+
+int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
+                     int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
+                     void* hip_stream) {
+  clear_error();
+  BatchView v;
+  int rc = validate_side("kvm_paged_decode", pool, reqs, false, &v);
+  if (rc) return rc;
+  if (v.n_req == 0 || v.total_blocks == 0) return KVM_OK;
+  if (!q_dev || !out_dev) return fail(KVM_EINVAL, "kvm_paged_decode: q_dev or out_dev is NULL");
+  if ((uintptr_t)q_dev % 16 || (uintptr_t)out_dev % 4)
+    return fail(KVM_EINVAL, "kvm_paged_decode: q_dev must be 16-byte and out_dev 4-byte aligned");
+  if (!(scale >= 0.f) || !std::isfinite(scale))
+    return fail(KVM_EINVAL, "kvm_paged_decode: scale must be finite and >= 0");
+  const kvm_layout& l = pool->layout;
+  if (l.block_tokens != 16 || (l.head_dim != 64 && l.head_dim != 128))
+    return fail(KVM_EINVAL, "kvm_paged_decode: supported shapes are block_tokens 16, head_dim 64 or 128");
+  int max_nb = 0;
+  for (int r = 0; r < v.n_req; ++r) max_nb = std::max(max_nb, v.nb[r]);
+  DecodePlan p = plan_decode(l, v.n_req, max_nb);
+  if (p.n_splits > 1) {
+    // an absent or short workspace only limits how far the context is split
+    const int64_t per_split = ws_bytes_for(l, v.n_req, 1);
+    int64_t fit = (workspace_dev && (uintptr_t)workspace_dev % 16 == 0) ? workspace_bytes / per_split : 0;
+    if (fit < 2) fit = 1;
+    p.n_splits = (int)std::min<int64_t>(p.n_splits, fit);
+  }
+
+  DecArgs a;
+  memset(&a, 0, sizeof a);
+  a.base = (const char*)pool->base;
+  a.bt = reqs->bt_blocks_dev;
+  a.stride_layer = l.stride_layer * 2;
+  a.stride_kv = l.stride_kv * 2;
+  a.stride_block = l.stride_block * 2;
+  a.stride_head = (uint32_t)(l.stride_head * 2);
+  a.stride_slot = (uint32_t)(l.stride_slot * 2);
+  a.q = (const uint16_t*)q_dev;
+  a.out = out_dev;
+  a.ws = (float*)workspace_dev;
+  a.L = l.n_layers;
+  a.H = l.n_kv_heads;
+  a.Hq = l.n_q_heads;
+  a.passes = p.passes;
+  a.n_splits = p.n_splits;
+  a.out_f32 = out_is_f32 ? 1 : 0;
+  const float sc = scale == 0.f ? 1.0f / std::sqrt((float)l.head_dim) : scale;
+  a.scale_log2e = sc * 1.4426950408889634f;
+
+  for (int r0 = 0; r0 < v.n_req; r0 += kMaxReqPerLaunch) {
+    const int n = std::min(kMaxReqPerLaunch, v.n_req - r0);
+    for (int i = 0; i < n; ++i) {
+      a.req[i].bt = v.bt_off[r0 + i];
+      a.req[i].k = v.k[r0 + i];
+      a.req[i].row = r0 + i;
+    }
+    hipError_t e;
+    const hipStream_t st = (hipStream_t)hip_stream;
+    const bool bf = l.dtype == KVM_BF16;
+    if (l.head_dim == 128)
+      e = bf ? launch_decode<128, 16, true>(a, p, n, st) : launch_decode<128, 16, false>(a, p, n, st);
+    else
+      e = bf ? launch_decode<64, 16, true>(a, p, n, st) : launch_decode<64, 16, false>(a, p, n, st);
+    if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
+  }
+  return KVM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Internal declarations shared by the host and device translation units of libkvm.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "kvm.h"
+
+namespace kvm {
+
+// Requests carried by one kernel launch.  Their descriptors travel in the kernel
+// argument segment, so the library needs no device-side metadata buffer.
+constexpr int kMaxReqPerLaunch = 64;
+
+// Records the failure detail for kvm_last_error() and returns `status`.
+int fail(int status, const std::string& msg);
+void clear_error();
+
+bool layout_ok(const kvm_layout* l, std::string* why);
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// One side of a transfer after validation: for every request the table offset,
+// k and the number of blocks that hold tokens [0,k).
+struct BatchView {
+  int n_req = 0;
+  std::vector<int32_t> bt_off;  // first table entry of request r
+  std::vector<int32_t> k;
+  std::vector<int32_t> nb;      // ceil(k / B)
+  int64_t total_tokens = 0;
+  int64_t total_blocks = 0;
+};
+
+// Checks pool + batch (pointers, alignment, layout, offsets, k range, id range).
+// `writing`: also reject an id that appears twice among the entries that will be
+// written.  On success fills `out`.
+int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch, bool writing,
+                  BatchView* out);
+
+struct Options {
+  int copy_unroll = 8;        // 16-byte vectors per lane per pass
+  int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
+  int copy_plane_major = 1;   // workgroup order: plane outermost
+  int decode_max_splits = 16;
+  int decode_force_splits = 0;  // > 0: use exactly this many context splits
+};
+Options& options();
+
+}  // namespace kvm

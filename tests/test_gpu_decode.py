@@ -1,0 +1,152 @@
+"""GPU parity: kvm_paged_decode through the C ABI against the fp64 CPU oracle.
+
+Bar: inputs fp16 / bf16, fp32 accumulation, fp32 output within 2e-3 absolute of
+the fp64 oracle.  A 16-bit output is compared with the oracle rounded to that
+type with one unit in the last place of slack.  Decode over a migrated copy must
+equal decode over the source bit for bit, because the kernel's reduction order
+depends on logical token positions only.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvm_workload as wl
+import paper_2501_06709_amd as kvm
+
+from gpu_util import DEV, Side, make_pair, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def gpu_decode(side, q, out_f32=True, scale=0.0, workspace=True, batch=None):
+    m = side.m
+    batch = batch or side.batch
+    q_dev = to_dev(q)
+    out = torch.full(q.shape, 7.0, dtype=torch.float32, device=DEV) if out_f32 else \
+        torch.zeros(q.shape, dtype=torch.int16, device=DEV)
+    ws = None
+    nbytes = kvm.kvm_decode_workspace_bytes(side.layout, batch)
+    if workspace and nbytes > 0:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    kvm.kvm_paged_decode(side.pool, batch, q_dev, out, out_is_f32=out_f32, scale=scale, workspace=ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_decode(orc, side, q, scale=None):
+    m = side.m
+    return orc.paged_decode(side.host, side.st, m.L, m.H, m.Hq, m.D, m.B, m.dtype, side.off,
+                            side.blk, side.k, q, scale=scale)
+
+
+SHAPES = [
+    wl.Model("tiny", 2, 4, 4, 64, 16, "f16"),
+    wl.Model("mha128", 2, 3, 3, 128, 16, "f16"),
+    wl.Model("gqa4", 2, 2, 8, 128, 16, "bf16"),
+    wl.Model("gqa2", 1, 2, 4, 64, 16, "bf16"),
+    wl.Model("gqa8", 1, 1, 8, 128, 16, "f16"),
+    wl.Model("gqa3", 1, 2, 6, 64, 16, "f16"),
+]
+
+
+@pytest.mark.parametrize("m", SHAPES, ids=[s.name for s in SHAPES])
+def test_decode_matches_oracle(oracle, m):
+    lens = [1, 15, 16, 17, 100, 333, 64]
+    src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=21, finite=True)
+    side = Side(m, 64, src.host, src.tables, lens)
+    q = wl.gen_q(21, m, len(lens))
+    got = gpu_decode(side, q)
+    ref = oracle_decode(oracle, side, q)
+    assert np.abs(got - ref).max() < TOL, np.abs(got - ref).max()
+
+
+def test_decode_k0_rows_untouched_and_scale(oracle):
+    m = wl.Model("z", 2, 2, 4, 128, 16, "bf16")
+    lens = [40, 20, 9]
+    src, _ = make_pair(m, 16, 8, lens, [0, 0, 0], seed=22, finite=True)
+    side = Side(m, 16, src.host, src.tables, [40, 0, 9])
+    q = wl.gen_q(22, m, 3)
+    got = gpu_decode(side, q, scale=0.3)
+    ref = oracle_decode(oracle, side, q, scale=0.3)
+    assert (got[1] == 7.0).all()
+    assert np.abs(got[[0, 2]] - ref[[0, 2]]).max() < TOL
+
+
+@pytest.mark.parametrize("splits", [2, 3, 7, 64])
+def test_context_splits_match_unsplit_and_oracle(oracle, splits):
+    m = wl.Model("sp", 2, 2, 8, 128, 16, "f16")
+    lens = [700, 33, 250, 16]
+    src, _ = make_pair(m, 80, 8, lens, [0] * 4, seed=23, finite=True)
+    side = Side(m, 80, src.host, src.tables, lens)
+    q = wl.gen_q(23, m, len(lens))
+    ref = oracle_decode(oracle, side, q)
+    try:
+        kvm.kvm_set_option("decode.force_splits", splits)
+        assert kvm.kvm_decode_workspace_bytes(side.layout, side.batch) == \
+            len(lens) * m.L * m.Hq * splits * (m.D + 2) * 4
+        got = gpu_decode(side, q)
+        nows = gpu_decode(side, q, workspace=False)   # no workspace: falls back to one split
+        kvm.kvm_set_option("decode.force_splits", 1)
+        one = gpu_decode(side, q)
+    finally:
+        kvm.kvm_set_option("decode.force_splits", 0)
+    assert np.abs(got - ref).max() < TOL and np.abs(one - ref).max() < TOL
+    assert np.abs(got - one).max() < 1e-5
+    assert np.array_equal(nows, one)
+
+
+def test_sixteen_bit_output(oracle):
+    for m in (wl.Model("h", 1, 2, 2, 128, 16, "f16"), wl.Model("b", 1, 2, 8, 128, 16, "bf16")):
+        lens = [90, 5]
+        src, _ = make_pair(m, 16, 8, lens, [0, 0], seed=24, finite=True)
+        side = Side(m, 16, src.host, src.tables, lens)
+        q = wl.gen_q(24, m, 2)
+        got_bits = gpu_decode(side, q, out_f32=False).view(np.uint16)
+        got = wl.bits16_to_f64(got_bits, m.dtype)
+        ref = oracle_decode(oracle, side, q)
+        mbits = 10 if m.dtype == "f16" else 7
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0**-14))) - mbits)
+        assert (np.abs(got - ref) <= ulp).all(), (np.abs(got - ref) / ulp).max()
+
+
+def test_garbage_beyond_the_context_is_ignored(oracle):
+    """Slots >= k of the last block and blocks past it may hold NaN patterns."""
+    m = wl.Model("nan", 1, 2, 4, 128, 16, "bf16")
+    lens, ks = [48, 40], [37, 16]
+    src, _ = make_pair(m, 16, 8, lens, [0, 0], seed=26, finite=True)
+    host = src.host.copy()
+    p6 = host.reshape(m.L, 2, 16, m.H, m.B, m.D)
+    for tab, k in zip(src.tables, ks):
+        for j, b in enumerate(tab):
+            p6[:, :, b, :, max(0, min(m.B, k - j * m.B)):] = 0x7FFF
+    side = Side(m, 16, host, src.tables, ks)
+    clean = Side(m, 16, src.host, src.tables, ks)
+    q = wl.gen_q(26, m, 2)
+    got = gpu_decode(side, q)
+    assert np.array_equal(got, gpu_decode(clean, q))
+    assert np.abs(got - oracle_decode(oracle, clean, q)).max() < TOL
+
+
+def test_decode_after_migration_is_bitwise_the_same(oracle):
+    """The usability proof: attention over the destination cache equals attention
+    over the first k tokens of the source cache."""
+    m = wl.LLAMA3_8B
+    m = wl.Model("8b4", 4, m.H, m.Hq, m.D, m.B, m.dtype)
+    lens, ks = [300, 49, 130], [225, 36, 97]
+    src, dst = make_pair(m, 48, 48, lens, ks, seed=25, finite=True)
+    kvm.kvm_migrate(src.pool, src.batch, dst.pool, dst.batch)
+    q = wl.gen_q(25, m, len(ks))
+    a = gpu_decode(src, q)
+    b = gpu_decode(dst, q)
+    assert np.array_equal(a, b)
+    ref = oracle_decode(oracle, src, q)
+    assert np.abs(a - ref).max() < TOL
+    # strided (token-major, padded) pool holding the same logical cache
+    slot = m.H * m.D + 8
+    tm = np.array([2 * m.B * slot, m.B * slot, m.L * 2 * m.B * slot, m.D, slot], dtype=np.int64)
+    alt_host = np.zeros(wl.pool_span_elems(m, 48, tm), dtype=np.uint16)
+    alt = Side(m, 48, alt_host, dst.tables, ks, strides=tm)
+    kvm.kvm_migrate(src.pool, src.batch, alt.pool, alt.batch)
+    c = gpu_decode(alt, q)
+    assert np.array_equal(a, c)

@@ -1,0 +1,373 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV migration hot path on one MI355X.
+
+A step is one pass of the whole path over the batch of requests to migrate:
+  a1  destination blocks popped from the destination free list, new block table
+      uploaded;
+  a2  kvm_pack   (gather into the staging buffer)
+  a4  kvm_unpack (scatter the staging buffer into the destination blocks)
+  a5  kvm_migrate (the same move fused, no staging; same destination tables)
+  a7  kvm_paged_decode over the destination cache
+  a6  source blocks returned to the source free list once the copies are done
+followed by the bookkeeping that lets the next step start from the same state
+(source ids reserved again, destination ids freed).  All of it is inside the
+timed region.
+
+`value` = bytes read + written by pack, unpack and fused migrate (6 x payload per
+step) divided by the whole step time (decode check and host steps are in the
+time, not in the bytes), in GB/s.  `roofline` is the fused migrate kernel alone:
+2 x payload / its average duration measured with HIP events on the launch
+stream inside the timed region.  `cpu_baseline` times the CPU oracle on a stated
+sample of the same workload, same byte accounting.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per fused-migrate launch, measured with rocprofv3 --pmc (a FETCH_SIZE
+# run and a WRITE_SIZE run, each scaled by what the same counter reads for the
+# plain copy kernel of known size in the same run); the counter summaries are in
+# profiles/kvm_migrate_llama3_8b_gqa_pmc_hbm.md.  Workloads without a measurement
+# report null.
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_gqa": 7986271556}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="llama3_8b_gqa")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=16, help="requests in the oracle's sample")
+    ap.add_argument("--unroll", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--order", type=int, default=None)
+    ap.add_argument("--no-verify", action="store_true")
+    return ap.parse_args()
+
+
+def fit_pools(w, free_bytes, extra_bytes, log):
+    """Shrink the pools (never the requests) when 2 pools + staging exceed HBM."""
+    m = w.model
+    need = (w.n_blocks_src + w.n_blocks_dst) * m.block_bytes + extra_bytes
+    budget = free_bytes - (3 << 30)
+    if need <= budget:
+        return w
+    import kvm_workload as wl
+    scale = (budget - extra_bytes) / ((w.n_blocks_src + w.n_blocks_dst) * m.block_bytes)
+    nbs, nbd = int(w.n_blocks_src * scale), int(w.n_blocks_dst * scale)
+    log("pools shrunk to fit HBM: src %d -> %d blocks, dst %d -> %d blocks"
+        % (w.n_blocks_src, nbs, w.n_blocks_dst, nbd))
+    w2 = wl.make(w.name, n_blocks_src=nbs, n_blocks_dst=nbd)
+    w2.notes.append("pools shrunk to fit HBM: src %d, dst %d blocks" % (nbs, nbd))
+    return w2
+
+
+def cpu_baseline(w, src_mem, staging_bytes_per_token, n_sample, log):
+    """Time the oracle (pack, unpack, migrate, decode) on the first n_sample
+    migrated requests, on a compact host pool holding only their blocks."""
+    import concurrent.futures as cf
+
+    import numpy as np
+    import torch
+
+    import kvm_workload as wl
+    from oracle import oracle as orc
+
+    m = w.model
+    n_sample = min(n_sample, len(w.k))
+    ks = w.k[:n_sample]
+    tabs = [w.src_tables[i] for i in w.migrate_ids[:n_sample]]
+    nbk = [-(-int(k) // m.B) for k in ks]
+    used = np.concatenate([t[:n] for t, n in zip(tabs, nbk)]).astype(np.int64)
+    n_loc = len(used)
+    # compact host source pool: the sampled blocks, in a seeded shuffled order
+    rng = np.random.default_rng(w.seed)
+    order = rng.permutation(n_loc).astype(np.int32)     # local id of the i-th used block
+    run = m.H * m.B * m.D
+    planes = src_mem.view(torch.int16).view(2 * m.L, w.n_blocks_src, run)
+    host_src = np.empty((2 * m.L, n_loc, run), dtype=np.uint16)
+    idx = torch.from_numpy(used).to(src_mem.device)
+    inv = np.empty(n_loc, dtype=np.int64)
+    inv[order] = np.arange(n_loc)
+    for p in range(2 * m.L):
+        host_src[p, order] = planes[p].index_select(0, idx).cpu().numpy().view(np.uint16)
+    host_src = host_src.reshape(-1)
+    host_dst = np.zeros_like(host_src)
+    st = orc.canonical_strides(m.L, m.H, m.D, m.B, n_loc)
+    s_tabs, p = [], 0
+    for n in nbk:
+        s_tabs.append(order[p:p + n].copy())
+        p += n
+    d_ids = orc.FreeList(n_loc).alloc(n_loc)
+    d_tabs, p = [], 0
+    for n in nbk:
+        d_tabs.append(np.array(d_ids[p:p + n], dtype=np.int32))
+        p += n
+    q = wl.gen_q(w.seed, m, n_sample)
+    threads = min(16, os.cpu_count() or 1)
+    payload = int(ks.astype(np.int64).sum()) * m.bytes_per_token
+    stage = [np.zeros(orc.staging_elems(m.L, m.H, m.D, [k]), dtype=np.uint16) for k in ks]
+
+    def one(r):
+        return [0, len(s_tabs[r])], s_tabs[r], [0, len(d_tabs[r])], d_tabs[r], [int(ks[r])]
+
+    def copy_unit(args):
+        r, l = args
+        so, sb, do, db, k = one(r)
+        orc.pack(host_src, st, m.L, m.H, m.D, m.B, so, sb, k, stage=stage[r], layers=(l, l + 1))
+        orc.unpack(stage[r], host_dst, st, m.L, m.H, m.D, m.B, do, db, k, layers=(l, l + 1))
+        orc.migrate(host_src, st, host_dst, st, m.L, m.H, m.D, m.B, so, sb, do, db, k,
+                    layers=(l, l + 1))
+
+    def decode_unit(r):
+        so, sb, do, db, k = one(r)
+        return orc.paged_decode(host_dst, st, m.L, m.H, m.Hq, m.D, m.B, m.dtype, do, db, k,
+                                q[r:r + 1])
+
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(threads) as ex:
+        list(ex.map(copy_unit, [(r, l) for r in range(n_sample) for l in range(m.L)]))
+        t1 = time.perf_counter()
+        list(ex.map(decode_unit, range(n_sample)))
+    t2 = time.perf_counter()
+    log("cpu oracle: %d requests, payload %.1f MiB, copies %.2f s, decode %.2f s on %d threads"
+        % (n_sample, payload / 2**20, t1 - t0, t2 - t1, threads))
+    return {"value": round(6 * payload / (t2 - t0) / 1e9, 4), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "first %d of %d migrated requests (%d tokens, %.1f MiB payload); pack+unpack+"
+                      "migrate over (request, layer) units, fp64 decode over requests; copies %.2f s,"
+                      " decode %.2f s" % (n_sample, len(w.k), int(ks.sum()), payload / 2**20,
+                                          t1 - t0, t2 - t1)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: the migration path here has no multi-GPU part "
+              "(--gpus %d refused)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+
+    import kvm_workload as wl
+    import paper_2501_06709_amd as kvm
+    from kvm_workload import device as wl_device
+
+    kvm.lib()  # fails loudly if the HIP library is not built
+    for name, val in (("copy.unroll", a.unroll), ("copy.nontemporal", a.nontemporal),
+                      ("copy.order", a.order)):
+        if val is not None:
+            kvm.kvm_set_option(name, val)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.make(a.config)
+    m = w.model
+    payload = w.payload_bytes()
+    free_b, total_b = torch.cuda.mem_get_info()
+    log("HBM free %.1f GiB of %.1f GiB; workload %s payload %.2f GiB"
+        % (free_b / 2**30, total_b / 2**30, w.name, payload / 2**30))
+    w = fit_pools(w, free_b, payload + (1 << 30), log)
+    payload = w.payload_bytes()
+
+    lay_s = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_src)
+    lay_d = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_dst)
+    src_mem = torch.empty(kvm.kvm_pool_span_bytes(lay_s, w.n_blocks_src), dtype=torch.uint8, device=dev)
+    dst_mem = torch.empty(kvm.kvm_pool_span_bytes(lay_d, w.n_blocks_dst), dtype=torch.uint8, device=dev)
+    t0 = time.perf_counter()
+    wl_device.fill_pool(src_mem, m, w.n_blocks_src, w.seed, wl.STREAM_SRC)
+    wl_device.fill_pool(dst_mem, m, w.n_blocks_dst, w.seed, wl.STREAM_DST)
+    torch.cuda.synchronize()
+    log("pools: src %d blocks (%.1f GiB), dst %d blocks (%.1f GiB), filled in %.2f s"
+        % (w.n_blocks_src, src_mem.numel() / 2**30, w.n_blocks_dst, dst_mem.numel() / 2**30,
+           time.perf_counter() - t0))
+    src_pool = kvm.Pool(src_mem, w.n_blocks_src, lay_s)
+    dst_pool = kvm.Pool(dst_mem, w.n_blocks_dst, lay_d)
+
+    # source side: tables of the migrated requests; free list = blocks no live request holds
+    s_off, s_blk = w.src_csr()
+    s_blk_dev = torch.from_numpy(s_blk).to(dev)
+    src_batch = kvm.Batch(s_off, s_blk, w.k, s_blk_dev)
+    src_occ = np.zeros(w.n_blocks_src, np.uint8)
+    src_occ[np.concatenate(w.src_tables)] = 1
+    src_fl = kvm.FreeList(w.n_blocks_src, src_occ)
+    dst_fl = kvm.FreeList(w.n_blocks_dst, w.dst_occupied)
+
+    nbk = w.n_dst_blocks()
+    n_dst = int(sum(nbk))
+    d_off = np.zeros(len(nbk) + 1, np.int32)
+    d_off[1:] = np.cumsum(nbk)
+    d_blk_pin = torch.empty(max(n_dst, 1), dtype=torch.int32, pin_memory=True)
+    d_blk_dev = torch.empty(max(n_dst, 1), dtype=torch.int32, device=dev)
+    staging = torch.empty(max(payload, 16), dtype=torch.uint8, device=dev)
+    q_host = wl.gen_q(w.seed, m, len(w.k))
+    q_dev = torch.from_numpy(q_host.view(np.int16)).to(dev)
+    out = torch.zeros(q_host.shape, dtype=torch.float32, device=dev)
+    probe = kvm.Batch(d_off, np.zeros(n_dst, np.int32), w.k, d_blk_dev)
+    ws_bytes = kvm.kvm_decode_workspace_bytes(lay_d, probe)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    names = ("pack", "unpack", "migrate", "decode")
+    stream = torch.cuda.current_stream()
+
+    def step(events):
+        # a1: allocate destination blocks, rewrite and upload the block table
+        ids = dst_fl.alloc(n_dst)
+        d_blk_pin.numpy()[:n_dst] = ids
+        d_blk_dev.copy_(d_blk_pin, non_blocking=True)
+        dst_batch = kvm.Batch(d_off, ids, w.k, d_blk_dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
+        if ev:
+            ev[0].record(stream)
+        kvm.kvm_pack(src_pool, src_batch, staging, staging_bytes=payload)          # a2
+        if ev:
+            ev[1].record(stream)
+        kvm.kvm_unpack(staging, dst_pool, dst_batch, staging_bytes=payload)        # a4
+        if ev:
+            ev[2].record(stream)
+        kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch)                  # a5
+        if ev:
+            ev[3].record(stream)
+        done = torch.cuda.Event()
+        done.record(stream)
+        kvm.kvm_paged_decode(dst_pool, dst_batch, q_dev, out, workspace=ws,
+                             workspace_bytes=ws_bytes)                              # a7
+        if ev:
+            ev[4].record(stream)
+            events.append(ev)
+        # a6: the source blocks may be released only once the copies have finished
+        done.synchronize()
+        src_fl.free(s_blk)
+        # bookkeeping so that the next step starts from the same state
+        src_fl.reserve(s_blk)
+        dst_fl.free(ids)
+        return ids
+
+    for _ in range(a.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        ids = step(events)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_step = t_total * 1e3 / a.steps
+    kern_ms = {n: float(np.mean([ev[i].elapsed_time(ev[i + 1]) for ev in events]))
+               for i, n in enumerate(names)}
+    log("step %.3f ms; kernels (ms): %s" % (ms_step, {k: round(v, 4) for k, v in kern_ms.items()}))
+
+    # practical ceiling: a plain contiguous device-to-device copy of the same payload
+    tmp = torch.empty_like(staging)
+    nb16 = payload // 16 * 16
+    for _ in range(2):
+        wl_device.plain_copy(tmp, staging, nb16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(5):
+        wl_device.plain_copy(tmp, staging, nb16)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    memcpy_gbs = 2 * nb16 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del tmp
+
+    # end-state check on sampled blocks: destination equals source, source equals generator
+    verified = None
+    if not a.no_verify:
+        run = m.H * m.B * m.D
+        sp = src_mem.view(torch.int16).view(2 * m.L, w.n_blocks_src, run)
+        dp = dst_mem.view(torch.int16).view(2 * m.L, w.n_blocks_dst, run)
+        rng = np.random.default_rng(1)
+        bad = 0
+        for _ in range(16):
+            r = int(rng.integers(len(w.k)))
+            if nbk[r] == 0:
+                continue
+            j = int(rng.integers(nbk[r]))
+            p = int(rng.integers(2 * m.L))
+            ns = min(m.B, int(w.k[r]) - j * m.B)
+            sblk = int(s_blk[s_off[r] + j])
+            dblk = int(ids[d_off[r] + j])
+            s_h = sp[p, sblk].cpu().numpy().view(np.uint16).reshape(m.H, m.B, m.D)
+            d_h = dp[p, dblk].cpu().numpy().view(np.uint16).reshape(m.H, m.B, m.D)
+            gen_s = wl.gen_block(w.seed, wl.STREAM_SRC, m, p, sblk)
+            gen_d = wl.gen_block(w.seed, wl.STREAM_DST, m, p, dblk)
+            ok = (np.array_equal(s_h, gen_s) and np.array_equal(d_h[:, :ns], gen_s[:, :ns])
+                  and np.array_equal(d_h[:, ns:], gen_d[:, ns:]))
+            bad += 0 if ok else 1
+        verified = bad == 0
+        log("sampled end-state check: %s" % ("ok" if verified else "%d MISMATCHES" % bad))
+
+    value = 6 * payload / (ms_step * 1e-3) / 1e9
+    mig_gbs = 2 * payload / (kern_ms["migrate"] * 1e-3) / 1e9
+    result = {
+        "metric": "KV migrate GB/s (read+write)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name,
+            "shape": "L%d H%d Hq%d D%d B%d %s" % (m.L, m.H, m.Hq, m.D, m.B, m.dtype),
+            "pool_blocks": [w.n_blocks_src, w.n_blocks_dst],
+            "live_requests": len(w.lens),
+            "migrated_requests": len(w.k),
+            "migrated_tokens": int(w.k.sum()),
+            "migrated_blocks": n_dst,
+            "payload_bytes": payload,
+            "value_is": "bytes read+written by pack, unpack and fused migrate (6 x payload) per "
+                        "second of whole-step time; the step also allocates, uploads the table, "
+                        "runs paged decode over the destination and releases the source",
+            "notes": w.notes,
+        },
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "migrated_blocks_per_s": round(n_dst / (kern_ms["migrate"] * 1e-3), 1),
+        "kernels": {
+            "pack": {"ms": round(kern_ms["pack"], 4),
+                     "GB/s": round(2 * payload / kern_ms["pack"] / 1e6, 1)},
+            "unpack": {"ms": round(kern_ms["unpack"], 4),
+                       "GB/s": round(2 * payload / kern_ms["unpack"] / 1e6, 1)},
+            "migrate": {"ms": round(kern_ms["migrate"], 4), "GB/s": round(mig_gbs, 1)},
+            "decode": {"ms": round(kern_ms["decode"], 4),
+                       "GB/s": round(payload / kern_ms["decode"] / 1e6, 1)},
+            "plain_copy": {"GB/s": round(memcpy_gbs, 1), "bytes": nb16},
+        },
+        "verified": verified,
+        "roofline": {
+            "kernel": "copy_kernel<migrate> (kvm_migrate)",
+            "bound": "hbm",
+            "achieved": round(mig_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(mig_gbs / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+        },
+    }
+    if not a.no_cpu_baseline:
+        del staging
+        result["cpu_baseline"] = cpu_baseline(w, src_mem, m.bytes_per_token, a.cpu_sample, log)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

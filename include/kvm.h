@@ -186,6 +186,10 @@ int kvm_freelist_alloc(kvm_freelist* fl, int32_t n, int32_t* out_ids);
 /* Return ids to the list.  KVM_EINVAL (and no change) if an id is out of
  * range, already free, or repeated in `ids`. */
 int kvm_freelist_free(kvm_freelist* fl, int32_t n, const int32_t* ids);
+/* Take exactly these ids off the list (rebuilding a list from existing block
+ * tables).  KVM_EINVAL (and no change) if an id is out of range, not free, or
+ * repeated in `ids`. */
+int kvm_freelist_reserve(kvm_freelist* fl, int32_t n, const int32_t* ids);
 
 /* ---- diagnostics ---------------------------------------------------------- */
 const char* kvm_strerror(int status);
@@ -194,9 +198,10 @@ const char* kvm_strerror(int status);
 const char* kvm_last_error(void);
 /* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
  * value gives KVM_EINVAL.  Names: "copy.unroll" (1,2,4,8 16-byte vectors per
- * lane per workgroup pass), "copy.nontemporal" (0/1), "copy.plane_major" (0/1:
- * workgroup order, plane or block outermost), "decode.max_splits" (1..64),
- * "decode.force_splits" (0 = automatic, else exactly this many context splits).
+ * lane per workgroup pass, 0 = automatic), "copy.nontemporal" (0/1), "copy.order" (0..5: how
+ * consecutive workgroups walk chunk / plane / block entry), "copy.lds_pad_kb"
+ * (0..64: dynamic LDS per workgroup, caps residency), "decode.max_splits"
+ * (1..64), "decode.force_splits" (0 = automatic, else exactly this many splits).
  * Process-wide; not thread-safe against concurrent launches. */
 int kvm_set_option(const char* name, int64_t value);
 

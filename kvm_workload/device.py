@@ -30,7 +30,19 @@ def _load():
         _lib.kvmw_fill_pool.restype = ctypes.c_int
         _lib.kvmw_fill_pool.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 5 + [
             ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p]
+        _lib.kvmw_plain_copy.restype = ctypes.c_int
+        _lib.kvmw_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_void_p]
     return _lib
+
+
+def plain_copy(dst, src, nbytes):
+    """Contiguous device copy of nbytes (multiple of 16) on the current stream."""
+    import torch
+    rc = _load().kvmw_plain_copy(dst.data_ptr(), src.data_ptr(), int(nbytes),
+                                 torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("kvmw_plain_copy failed with %d" % rc)
 
 
 def fill_pool(mem, model, n_blocks, seed, stream_id, strides=None, b0=0, b1=None):

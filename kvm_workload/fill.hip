@@ -96,3 +96,25 @@ extern "C" int kvmw_fill_pool(void* base_dev, const int64_t* strides_bytes, int 
   }
   return 0;
 }
+
+// Plain contiguous device-to-device copy of `bytes` (multiple of 16) with 16-byte
+// vectors, 4 KiB per workgroup: the reference the benchmark reports beside the
+// gather/scatter kernels, and a kernel of known size for scaling HBM counters.
+typedef unsigned int kvmw_v4u __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void plain_copy_kernel(const char* src, char* dst, uint64_t n_vec) {
+  const uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (v < n_vec) {
+    const kvmw_v4u x = __builtin_nontemporal_load(reinterpret_cast<const kvmw_v4u*>(src) + v);
+    __builtin_nontemporal_store(x, reinterpret_cast<kvmw_v4u*>(dst) + v);
+  }
+}
+
+extern "C" int kvmw_plain_copy(void* dst_dev, const void* src_dev, int64_t bytes, void* hip_stream) {
+  if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16) return -1;
+  const uint64_t n_vec = (uint64_t)bytes / 16;
+  const uint64_t grid = (n_vec + 255) / 256;
+  if (grid > 0x7fffffffull) return -1;
+  hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const char*)src_dev, (char*)dst_dev, n_vec);
+  return (int)hipGetLastError();
+}

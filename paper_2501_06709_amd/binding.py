@@ -88,6 +88,8 @@ def lib():
         L.kvm_freelist_alloc.argtypes = [VP, I32, VP]
         L.kvm_freelist_free.restype = ctypes.c_int
         L.kvm_freelist_free.argtypes = [VP, I32, VP]
+        L.kvm_freelist_reserve.restype = ctypes.c_int
+        L.kvm_freelist_reserve.argtypes = [VP, I32, VP]
         L.kvm_strerror.restype = ctypes.c_char_p
         L.kvm_strerror.argtypes = [ctypes.c_int]
         L.kvm_last_error.restype = ctypes.c_char_p
@@ -232,6 +234,10 @@ class FreeList:
     def free(self, ids):
         ids = np.ascontiguousarray(ids, dtype=np.int32)
         _check(lib().kvm_freelist_free(self._h, len(ids), ids.ctypes.data))
+
+    def reserve(self, ids):
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        _check(lib().kvm_freelist_reserve(self._h, len(ids), ids.ctypes.data))
 
     def close(self):
         if self._h:

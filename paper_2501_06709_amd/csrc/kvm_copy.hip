@@ -60,7 +60,7 @@ struct CopyArgs {
   int32_t H, B;
   uint32_t DV;         // 16-byte vectors per token row (head_dim*2/16)
   int32_t dv_shift;    // log2(DV) or -1
-  int32_t plane_major;
+  int32_t order;       // how consecutive workgroups walk (chunk, plane, block entry)
   CopyReq req[kMaxReqPerLaunch];
 };
 
@@ -80,25 +80,60 @@ template <int MODE, int U, bool NT>
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   // ---- decode the work item (all wave-uniform) ----
   uint32_t wg = blockIdx.x;
-  const uint32_t chunk = wg % (uint32_t)a.n_chunks;
-  wg /= (uint32_t)a.n_chunks;
-  uint32_t item, plane;
-  if (a.plane_major) {
-    item = wg % (uint32_t)a.n_items;
-    plane = wg / (uint32_t)a.n_items;
-  } else {
-    plane = wg % (uint32_t)a.n_planes;
-    item = wg / (uint32_t)a.n_planes;
+  uint32_t chunk = 0, item = 0, plane = 0;
+  switch (a.order) {
+    case 1:  // chunk fastest, then block entry, plane outermost
+      chunk = wg % (uint32_t)a.n_chunks; wg /= (uint32_t)a.n_chunks;
+      item = wg % (uint32_t)a.n_items; plane = wg / (uint32_t)a.n_items;
+      break;
+    case 2:  // plane fastest, then chunk, block entry outermost
+      plane = wg % (uint32_t)a.n_planes; wg /= (uint32_t)a.n_planes;
+      chunk = wg % (uint32_t)a.n_chunks; item = wg / (uint32_t)a.n_chunks;
+      break;
+    case 3:  // plane fastest, then block entry, chunk outermost
+      plane = wg % (uint32_t)a.n_planes; wg /= (uint32_t)a.n_planes;
+      item = wg % (uint32_t)a.n_items; chunk = wg / (uint32_t)a.n_items;
+      break;
+    case 5:
+      break;  // decoded below, once the request is known
+    case 4:  // block entry fastest, then chunk, plane outermost
+      item = wg % (uint32_t)a.n_items; wg /= (uint32_t)a.n_items;
+      chunk = wg % (uint32_t)a.n_chunks; plane = wg / (uint32_t)a.n_chunks;
+      break;
+    default:  // chunk fastest, then plane, block entry outermost
+      chunk = wg % (uint32_t)a.n_chunks; wg /= (uint32_t)a.n_chunks;
+      plane = wg % (uint32_t)a.n_planes; item = wg / (uint32_t)a.n_planes;
+      break;
   }
   // request that owns the item: largest r with first_item[r] <= item
   int r = 0;
+  int32_t j;
+  if (a.order == 5) {
+    // staging order: request outermost, then plane, chunk, and the request's
+    // blocks fastest, so consecutive workgroups walk the staging buffer linearly
+    const uint32_t per_item = (uint32_t)a.n_planes * (uint32_t)a.n_chunks;
+    wg = blockIdx.x;
 #pragma unroll
-  for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
-    const int t = r + s;
-    if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
+    for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
+      const int t = r + s;
+      if (t < a.n_req && (uint32_t)a.req[t].first_item * per_item <= wg) r = t;
+    }
+    const uint32_t nb_r = (uint32_t)((r + 1 < a.n_req ? a.req[r + 1].first_item : a.n_items) -
+                                     a.req[r].first_item);
+    wg -= (uint32_t)a.req[r].first_item * per_item;
+    j = (int32_t)(wg % nb_r);
+    wg /= nb_r;
+    chunk = wg % (uint32_t)a.n_chunks;
+    plane = wg / (uint32_t)a.n_chunks;
+  } else {
+#pragma unroll
+    for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
+      const int t = r + s;
+      if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
+    }
+    j = (int32_t)item - a.req[r].first_item;  // logical block of the request
   }
   const CopyReq rq = a.req[r];
-  const int32_t j = (int32_t)item - rq.first_item;  // logical block of the request
   const int32_t rem_tokens = rq.k - j * a.B;
   const uint32_t ns = rem_tokens < a.B ? (uint32_t)rem_tokens : (uint32_t)a.B;  // slots to move
   const uint32_t layer = plane >> 1, kv = plane & 1;
@@ -193,20 +228,30 @@ static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
   return s;
 }
 
+// 16-byte vectors per lane per workgroup.  The automatic choice is what measured
+// best on MI355X for 32 KiB..160 KiB block runs: 4 for the fused move, 1 for pack
+// (its 4 KiB staging runs favour small workgroup footprints), 8 for unpack.
+template <int MODE>
+static int pick_unroll() {
+  const int u = options().copy_unroll;
+  if (u) return u;
+  return MODE == kMigrate ? 4 : (MODE == kPack ? 1 : 8);
+}
+
 template <int MODE>
 static hipError_t launch(const CopyArgs& a, uint32_t grid, hipStream_t stream) {
   const Options& o = options();
 #define KVM_LAUNCH(U, NT) \
-  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), dim3(grid), dim3(256), 0, stream, a)
+  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), dim3(grid), dim3(256), (size_t)o.copy_lds_pad_kb * 1024, stream, a)
   if (o.copy_nontemporal) {
-    switch (o.copy_unroll) {
+    switch (pick_unroll<MODE>()) {
       case 1: KVM_LAUNCH(1, true); break;
       case 2: KVM_LAUNCH(2, true); break;
       case 4: KVM_LAUNCH(4, true); break;
       default: KVM_LAUNCH(8, true); break;
     }
   } else {
-    switch (o.copy_unroll) {
+    switch (pick_unroll<MODE>()) {
       case 1: KVM_LAUNCH(1, false); break;
       case 2: KVM_LAUNCH(2, false); break;
       case 4: KVM_LAUNCH(4, false); break;
@@ -238,8 +283,8 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   a.B = l.block_tokens;
   a.DV = (uint32_t)(l.head_dim * 2 / 16);
   a.dv_shift = ilog2_exact(a.DV);
-  a.plane_major = options().copy_plane_major;
-  const int U = options().copy_unroll;
+  a.order = options().copy_order;
+  const int U = pick_unroll<MODE>();
   const int64_t vec_per_item = (int64_t)l.n_kv_heads * l.block_tokens * a.DV;
   a.n_chunks = (int32_t)ceil_div(vec_per_item, (int64_t)U * 256);
   const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;  // vectors per token

@@ -239,6 +239,26 @@ int kvm_freelist_free(kvm_freelist* fl, int32_t n, const int32_t* ids) {
   return KVM_OK;
 }
 
+int kvm_freelist_reserve(kvm_freelist* fl, int32_t n, const int32_t* ids) {
+  if (!fl || n < 0 || (n > 0 && !ids)) return fail(KVM_EINVAL, "kvm_freelist_reserve: bad argument");
+  int32_t done = 0;
+  bool ok = true;
+  for (; done < n; ++done) {
+    const int64_t id = ids[done];
+    if (id < 0 || id >= fl->n_blocks) { ok = false; break; }
+    uint64_t& word = fl->bits[(size_t)id >> 6];
+    const uint64_t bit = 1ull << (id & 63);
+    if (!(word & bit)) { ok = false; break; }  // in use, or repeated in ids
+    word &= ~bit;
+  }
+  if (!ok) {
+    for (int32_t i = 0; i < done; ++i) fl->bits[(size_t)ids[i] >> 6] |= 1ull << (ids[i] & 63);
+    return fail(KVM_EINVAL, "kvm_freelist_reserve: id out of range, not free, or repeated");
+  }
+  fl->n_free -= n;
+  return KVM_OK;
+}
+
 const char* kvm_strerror(int status) {
   switch (status) {
     case KVM_OK: return "ok";
@@ -255,15 +275,18 @@ int kvm_set_option(const char* name, int64_t value) {
   if (!name) return fail(KVM_EINVAL, "kvm_set_option: name is NULL");
   Options& o = options();
   if (!strcmp(name, "copy.unroll")) {
-    if (value != 1 && value != 2 && value != 4 && value != 8)
-      return fail(KVM_EINVAL, "copy.unroll must be 1, 2, 4 or 8");
+    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+      return fail(KVM_EINVAL, "copy.unroll must be 0 (automatic), 1, 2, 4 or 8");
     o.copy_unroll = (int)value;
   } else if (!strcmp(name, "copy.nontemporal")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.nontemporal must be 0 or 1");
     o.copy_nontemporal = (int)value;
-  } else if (!strcmp(name, "copy.plane_major")) {
-    if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.plane_major must be 0 or 1");
-    o.copy_plane_major = (int)value;
+  } else if (!strcmp(name, "copy.order")) {
+    if (value < 0 || value > 5) return fail(KVM_EINVAL, "copy.order must be in [0,5]");
+    o.copy_order = (int)value;
+  } else if (!strcmp(name, "copy.lds_pad_kb")) {
+    if (value < 0 || value > 64) return fail(KVM_EINVAL, "copy.lds_pad_kb must be in [0,64]");
+    o.copy_lds_pad_kb = (int)value;
   } else if (!strcmp(name, "decode.max_splits")) {
     if (value < 1 || value > 64) return fail(KVM_EINVAL, "decode.max_splits must be in [1,64]");
     o.decode_max_splits = (int)value;

@@ -37,9 +37,10 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
                   BatchView* out);
 
 struct Options {
-  int copy_unroll = 8;        // 16-byte vectors per lane per pass
+  int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
-  int copy_plane_major = 1;   // workgroup order: plane outermost
+  int copy_order = 0;         // 0..3: how consecutive workgroups walk (chunk, plane, block)
+  int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits
 };

@@ -18,6 +18,7 @@ from gpu_util import (DEV, Side, csr, dev_table, make_pair, oracle_migrate, rand
                       to_host)
 
 pytestmark = pytest.mark.gpu
+DEFAULTS = (0, 1, 0)   # copy.unroll, copy.nontemporal, copy.order as the library ships
 
 
 def run_all_three(orc, src, dst):
@@ -93,19 +94,19 @@ def test_model_shapes_shrunken_pools(oracle, name, m, n_src, n_dst, lens, ks):
     run_all_three(oracle, src, dst)
 
 
-@pytest.mark.parametrize("unroll,nt,plane_major", [(1, 0, 1), (2, 1, 0), (4, 0, 0), (8, 1, 1)])
-def test_every_launch_option(oracle, unroll, nt, plane_major):
+@pytest.mark.parametrize("unroll,nt,order", [(1, 0, 1), (2, 1, 0), (4, 0, 2), (8, 1, 3), (2, 0, 4), (1, 1, 5), (8, 0, 5)])
+def test_every_launch_option(oracle, unroll, nt, order):
     try:
         kvm.kvm_set_option("copy.unroll", unroll)
         kvm.kvm_set_option("copy.nontemporal", nt)
-        kvm.kvm_set_option("copy.plane_major", plane_major)
+        kvm.kvm_set_option("copy.order", order)
         m = wl.Model("o", 3, 5, 5, 128, 16, "f16")   # 5 heads: 20 KiB runs, ragged against 32 KiB passes
         src, dst = make_pair(m, 40, 48, [200, 31, 64, 5], [150, 31, 64, 3], seed=unroll)
         run_all_three(oracle, src, dst)
     finally:
-        kvm.kvm_set_option("copy.unroll", 8)
-        kvm.kvm_set_option("copy.nontemporal", 1)
-        kvm.kvm_set_option("copy.plane_major", 1)
+        kvm.kvm_set_option("copy.unroll", DEFAULTS[0])
+        kvm.kvm_set_option("copy.nontemporal", DEFAULTS[1])
+        kvm.kvm_set_option("copy.order", DEFAULTS[2])
 
 
 def test_edge_cases_k(oracle):

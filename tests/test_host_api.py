@@ -170,6 +170,16 @@ def test_freelist_matches_oracle_allocator(oracle):
     assert list(fl.alloc(6)) == [1, 2, 4, 5, 6, 7]   # the failed frees changed nothing
     fl.free([0, 3])
     assert list(fl.alloc(2)) == [0, 3]
+    # reserve takes named ids off the list, all-or-nothing
+    fl = kvm.FreeList(8, [1, 0, 0, 1, 0, 0, 0, 0])
+    fl.reserve([2, 6])
+    assert fl.available() == 4 and list(fl.alloc(2)) == [1, 4]
+    for bad in ([2], [0], [5, 5], [8], [7, 6]):
+        before = fl.available()
+        with pytest.raises(kvm.KvmError) as e:
+            fl.reserve(bad)
+        assert e.value.status == kvm.KVM_EINVAL and fl.available() == before
+    assert list(fl.alloc(2)) == [5, 7]
     with pytest.raises(kvm.KvmError):
         kvm.FreeList(0)
 
@@ -181,5 +191,5 @@ def test_options_and_strerror():
                       ("decode.max_splits", 0), ("decode.force_splits", 65)):
         with pytest.raises(kvm.KvmError):
             kvm.kvm_set_option(name, val)
-    kvm.kvm_set_option("copy.unroll", 8)
+    kvm.kvm_set_option("copy.unroll", 0)
     kvm.kvm_set_option("decode.force_splits", 0)

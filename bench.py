@@ -180,7 +180,8 @@ def main():
     free_b, total_b = torch.cuda.mem_get_info()
     log("HBM free %.1f GiB of %.1f GiB; workload %s payload %.2f GiB"
         % (free_b / 2**30, total_b / 2**30, w.name, payload / 2**30))
-    w = fit_pools(w, free_b, payload + (1 << 30), log)
+    # room beside the pools: staging for at least the largest request, tables, q, out
+    w = fit_pools(w, free_b, int(w.k.max()) * m.bytes_per_token + (2 << 30), log)
     payload = w.payload_bytes()
 
     lay_s = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_src)
@@ -212,7 +213,25 @@ def main():
     d_off[1:] = np.cumsum(nbk)
     d_blk_pin = torch.empty(max(n_dst, 1), dtype=torch.int32, pin_memory=True)
     d_blk_dev = torch.empty(max(n_dst, 1), dtype=torch.int32, device=dev)
-    staging = torch.empty(max(payload, 16), dtype=torch.uint8, device=dev)
+    # The staged path needs a staging buffer; when the whole batch's does not fit
+    # beside the pools it is run in groups of consecutive requests.
+    free_now, _ = torch.cuda.mem_get_info()
+    stage_budget = max(free_now - (4 << 30), 1 << 20)
+    groups, g0, acc = [], 0, 0
+    for r, kr in enumerate(w.k):
+        b = int(kr) * m.bytes_per_token
+        if b > stage_budget:
+            raise SystemExit("one request's staging (%d B) does not fit in HBM" % b)
+        if acc + b > stage_budget:
+            groups.append((g0, r))
+            g0, acc = r, 0
+        acc += b
+    groups.append((g0, len(w.k)))
+    stage_bytes = max(int(w.k[lo:hi].astype(np.int64).sum()) * m.bytes_per_token for lo, hi in groups)
+    staging = torch.empty(max(stage_bytes, 16), dtype=torch.uint8, device=dev)
+    if len(groups) > 1:
+        log("staged path runs in %d request groups (staging buffer %.1f GiB)"
+            % (len(groups), stage_bytes / 2**30))
     q_host = wl.gen_q(w.seed, m, len(w.k))
     q_dev = torch.from_numpy(q_host.view(np.int16)).to(dev)
     out = torch.zeros(q_host.shape, dtype=torch.float32, device=dev)
@@ -220,6 +239,12 @@ def main():
     ws_bytes = kvm.kvm_decode_workspace_bytes(lay_d, probe)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
 
+    def sub_batch(off, blk, blk_dev, lo, hi):
+        """Requests [lo,hi) of a batch as a batch of their own (pointer arithmetic only)."""
+        o = off[lo:hi + 1] - off[lo]
+        return kvm.Batch(o, blk[off[lo]:off[hi]], w.k[lo:hi], blk_dev.data_ptr() + 4 * int(off[lo]))
+
+    src_groups = [sub_batch(s_off, s_blk, s_blk_dev, lo, hi) for lo, hi in groups]
     names = ("pack", "unpack", "migrate", "decode")
     stream = torch.cuda.current_stream()
 
@@ -229,25 +254,29 @@ def main():
         d_blk_pin.numpy()[:n_dst] = ids
         d_blk_dev.copy_(d_blk_pin, non_blocking=True)
         dst_batch = kvm.Batch(d_off, ids, w.k, d_blk_dev)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
-        if ev:
-            ev[0].record(stream)
-        kvm.kvm_pack(src_pool, src_batch, staging, staging_bytes=payload)          # a2
-        if ev:
-            ev[1].record(stream)
-        kvm.kvm_unpack(staging, dst_pool, dst_batch, staging_bytes=payload)        # a4
-        if ev:
-            ev[2].record(stream)
-        kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch)                  # a5
-        if ev:
-            ev[3].record(stream)
+        marks = []
+
+        def timed(name, fn):
+            if events is None:
+                return fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            marks.append((name, e0, e1))
+
+        for (lo, hi), sg in zip(groups, src_groups):
+            dg = dst_batch if len(groups) == 1 else sub_batch(d_off, ids, d_blk_dev, lo, hi)
+            nbytes = int(w.k[lo:hi].astype(np.int64).sum()) * m.bytes_per_token
+            timed("pack", lambda: kvm.kvm_pack(src_pool, sg, staging, staging_bytes=nbytes))    # a2
+            timed("unpack", lambda: kvm.kvm_unpack(staging, dst_pool, dg, staging_bytes=nbytes))  # a4
+        timed("migrate", lambda: kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch))      # a5
         done = torch.cuda.Event()
         done.record(stream)
-        kvm.kvm_paged_decode(dst_pool, dst_batch, q_dev, out, workspace=ws,
-                             workspace_bytes=ws_bytes)                              # a7
-        if ev:
-            ev[4].record(stream)
-            events.append(ev)
+        timed("decode", lambda: kvm.kvm_paged_decode(dst_pool, dst_batch, q_dev, out, workspace=ws,
+                                                     workspace_bytes=ws_bytes))                  # a7
+        if events is not None:
+            events.append(marks)
         # a6: the source blocks may be released only once the copies have finished
         done.synchronize()
         src_fl.free(s_blk)
@@ -266,23 +295,23 @@ def main():
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_step = t_total * 1e3 / a.steps
-    kern_ms = {n: float(np.mean([ev[i].elapsed_time(ev[i + 1]) for ev in events]))
-               for i, n in enumerate(names)}
+    kern_ms = {n: float(np.mean([sum(e0.elapsed_time(e1) for nm, e0, e1 in marks if nm == n)
+                                 for marks in events])) for n in names}
     log("step %.3f ms; kernels (ms): %s" % (ms_step, {k: round(v, 4) for k, v in kern_ms.items()}))
 
     # practical ceiling: a plain contiguous device-to-device copy of the same payload
-    tmp = torch.empty_like(staging)
-    nb16 = payload // 16 * 16
+    # (one half of the staging buffer copied onto the other: no extra allocation)
+    nb16 = min(payload, stage_bytes // 2) // 16 * 16
+    half_a, half_b = staging[:nb16], staging[nb16:2 * nb16]
     for _ in range(2):
-        wl_device.plain_copy(tmp, staging, nb16)
+        wl_device.plain_copy(half_b, half_a, nb16)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)
     for _ in range(5):
-        wl_device.plain_copy(tmp, staging, nb16)
+        wl_device.plain_copy(half_b, half_a, nb16)
     e1.record(stream)
     torch.cuda.synchronize()
     memcpy_gbs = 2 * nb16 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del tmp
 
     # end-state check on sampled blocks: destination equals source, source equals generator
     verified = None

@@ -66,3 +66,24 @@ def test_shrunken_configs_keep_structure():
                 len_cap=300)
     assert w.model is wl.LLAMA3_8B and len(w.k) == 3 and w.lens.max() <= 300
     assert np.concatenate(w.src_tables).max() < 512
+
+
+def test_mixed_scenario_structure():
+    from kvm_workload import mixed
+    sc = mixed.make()
+    assert [m.name for m in sc.models] == ["llama2_7b", "llama3_8b_gqa", "llama2_13b"]
+    assert len(sc.requests) == 512 and len(sc.orders) == 200
+    assert max(r.length for r in sc.requests) <= 16384
+    assert sc.arena_bytes < 260 * 2**30
+    for mi, m in enumerate(sc.models):
+        for h in range(2):
+            ids = np.concatenate([r.table for r in sc.requests if r.model == mi and r.half == h])
+            assert len(np.unique(ids)) == len(ids) and ids.max() < sc.half_blocks[mi]
+            assert 0.5 < mixed.occupancy(sc, mi, h).mean() < 0.8      # fragmented, not full
+            assert sc.half_offset[mi][h] % (2 << 20) == 0
+    ends = sorted((sc.half_offset[mi][h], sc.half_offset[mi][h] + sc.half_blocks[mi] * m.block_bytes)
+                  for mi, m in enumerate(sc.models) for h in range(2))
+    assert all(a[1] <= b[0] for a, b in zip(ends, ends[1:])) and ends[-1][1] <= sc.arena_bytes
+    assert all(0.5 <= u <= 1.0 and 0 <= r < 512 for r, u in sc.orders)
+    again = mixed.make()
+    assert [r.length for r in again.requests] == [r.length for r in sc.requests] and again.orders == sc.orders

@@ -150,6 +150,75 @@ def cpu_baseline(w, src_mem, staging_bytes_per_token, n_sample, log):
                                           t1 - t0, t2 - t1)}
 
 
+def bench_mixed(a, log):
+    """Multi-LLM mixed pool: the seeded order stream run back to back on one stream
+    (allocation, table upload, fused migrate, decode over the destination, deferred
+    source release), host overhead included.  One step = one order."""
+    import numpy as np
+    import torch
+
+    import kvm_workload as wl
+    import paper_2501_06709_amd as kvm
+    from kvm_workload import device as wl_device
+    from kvm_workload import mixed
+    from paper_2501_06709_amd.migrator import DevicePool, Migrator
+
+    dev = torch.device("cuda:0")
+    sc = mixed.make()
+    arena = torch.empty(sc.arena_bytes, dtype=torch.uint8, device=dev)
+    pools = []
+    for mi, m in enumerate(sc.models):
+        n = sc.half_blocks[mi]
+        lay = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, n)
+        halves = []
+        for h in range(2):
+            off = sc.half_offset[mi][h]
+            region = arena[off:off + n * m.block_bytes]
+            wl_device.fill_pool(region, m, n, sc.seed, sc.stream(mi, h))
+            halves.append(DevicePool(region, n, lay, mixed.occupancy(sc, mi, h)))
+        pools.append(halves)
+    qs = [torch.from_numpy(wl.gen_q(sc.seed, m, 1).view(np.int16)).to(dev) for m in sc.models]
+    outs = [torch.zeros(q.shape, dtype=torch.float32, device=dev) for q in qs]
+    torch.cuda.synchronize()
+    log("mixed arena %.1f GiB, %d requests, %d orders" % (sc.arena_bytes / 2**30, len(sc.requests),
+                                                          len(sc.orders)))
+    mig = Migrator(dev, max(len(r.table) for r in sc.requests))
+    moved = skipped = blocks = 0
+    nbytes = 0
+    t0 = time.perf_counter()
+    for ri, u in sc.orders:
+        rq = sc.requests[ri]
+        m = sc.models[rq.model]
+        k = int(np.floor(u * rq.length))
+        try:
+            ids = mig.move(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half],
+                           k, decode=(qs[rq.model], outs[rq.model], None, 0))
+        except kvm.KvmError:
+            skipped += 1
+            continue
+        rq.table, rq.length, rq.half = ids, k, 1 - rq.half
+        moved += 1
+        blocks += len(ids)
+        nbytes += 2 * k * m.bytes_per_token
+    mig.drain()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    log("%d orders moved (%d skipped) in %.1f ms" % (moved, skipped, dt * 1e3))
+    gbs = nbytes / dt / 1e9
+    print(json.dumps({
+        "metric": "KV migrate GB/s (read+write)", "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": moved, "warmup": 0, "ms_per_step": round(dt * 1e3 / max(moved, 1), 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": "mixed", "arena_bytes": sc.arena_bytes, "requests": len(sc.requests),
+                   "orders": len(sc.orders), "orders_skipped_no_blocks": skipped,
+                   "value_is": "2 x moved bytes per second of wall time over the whole order stream, "
+                               "decode over each destination and host work included"},
+        "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "orders_per_s": round(moved / dt, 1), "migrated_blocks_per_s": round(blocks / dt, 1),
+        "roofline": None}), flush=True)
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -174,6 +243,8 @@ def main():
             kvm.kvm_set_option(name, val)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if a.config == "mixed":
+        return bench_mixed(a, log)
     w = wl.make(a.config)
     m = w.model
     payload = w.payload_bytes()

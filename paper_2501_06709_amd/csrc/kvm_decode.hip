@@ -107,6 +107,25 @@ __device__ __forceinline__ void widen8(v4u raw, float* f) {
   }
 }
 
+// Dot product of eight 16-bit pairs-packed values with fp32 accumulation
+// (v_dot2c_f32_f16 / v_dot2c_f32_bf16: two multiply-adds per instruction).
+template <bool BF16>
+__device__ __forceinline__ float dot8(const uint32_t* qv, v4u kv) {
+  float acc = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const uint32_t x = qv[c], y = kv[c];
+    if (BF16) {
+      typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+      acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, x), __builtin_bit_cast(b2, y), acc, false);
+    } else {
+      typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+      acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, x), __builtin_bit_cast(h2, y), acc, false);
+    }
+  }
+  return acc;
+}
+
 template <bool BF16>
 __device__ __forceinline__ uint16_t narrow(float f) {
   if (BF16) {
@@ -158,15 +177,17 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   const int row = lane / LPT;
   const int hq0 = (h * a.passes + pass) * G;  // first query head served here
 
-  // query fragment: dims sub*8 .. sub*8+7 of each of the G heads, pre-scaled
-  float qf[G][8];
+  // query fragment: dims sub*8 .. sub*8+7 of each of the G heads, kept as four
+  // packed 16-bit pairs per head; the softmax scale is applied to the reduced score
+  uint32_t qp[G][4];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint16_t* qp = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0 + g) * D + sub * 8;
-    widen8<BF16>(*reinterpret_cast<const v4u*>(qp), qf[g]);
+    const uint16_t* qptr = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0 + g) * D + sub * 8;
+    const v4u raw = *reinterpret_cast<const v4u*>(qptr);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) qf[g][c] *= a.scale_log2e;
+    for (int c = 0; c < 4; ++c) qp[g][c] = raw[c];
   }
+  const float sc = a.scale_log2e;
 
   float m[G], lsum[G], o[G][8];
 #pragma unroll
@@ -190,52 +211,47 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
     const int j = jb + wave + 4 * (it0 + lane);
     ids = j < je ? a.bt[rq.bt + j] : 0;
   };
-  auto load_block = [&](int it, v4u* kd, v4u* vd) {
+  auto load_k = [&](int it, v4u* kd) {
     const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
     const char* kp = kbase + blk * a.stride_block + lane_off;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      kd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * inst_off));
+  };
+  auto load_v = [&](int it, v4u* vd) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
     const char* vp = vbase + blk * a.stride_block + lane_off;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      kd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * inst_off));
+    for (int i = 0; i < NI; ++i)
       vd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp + i * inst_off));
-    }
   };
 
+  // Software pipeline with one K and one V register tile: K of the next block is
+  // requested as soon as the scores of the current one are formed, V of the next
+  // block as soon as the current V rows are accumulated, so a load is always in
+  // flight while the other tile is being consumed.
   if (n_it > 0) {
     fetch_ids(0);
-    load_block(0, kc, vc);
+    load_k(0, kc);
+    load_v(0, vc);
   }
   for (int it = 0; it < n_it; ++it) {
-    v4u kn[NI], vn[NI];
     const bool more = it + 1 < n_it;
-    if (more) {
-      if (((it + 1) & 63) == 0) fetch_ids(it + 1);
-      load_block(it + 1, kn, vn);
-    }
     const int j = jb + wave + 4 * it;
     const int t_limit = k - j * B;  // slots >= t_limit of this block are not context
-    if (t_limit < B) {
-      // Slots past the context may hold anything (NaN patterns included): clear
-      // their V rows so that a zero weight cannot turn them into NaN.
-#pragma unroll
-      for (int i = 0; i < NI; ++i)
-        if (i * TPI + row >= t_limit) vc[i] = v4u{0u, 0u, 0u, 0u};
-    }
 
     float s[NI][G];
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      float kf[8];
-      widen8<BF16>(kc[i], kf);
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float acc = qf[g][0] * kf[0];
-#pragma unroll
-        for (int c = 1; c < 8; ++c) acc = fmaf(qf[g][c], kf[c], acc);
-        s[i][g] = group_sum<LPT>(acc);
-      }
+      for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i])) * sc;
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      if (((it + 1) & 63) == 0) fetch_ids(it + 1);
+      load_k(it + 1, kc);
     }
-    float p[NI][G];
+    __builtin_amdgcn_sched_barrier(0);
+
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float mx = m[g];
@@ -247,12 +263,19 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
       float add = 0.f;
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        p[i][g] = (i * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[i][g] - mx) : 0.f;
-        add += p[i][g];
+        s[i][g] = (i * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[i][g] - mx) : 0.f;
+        add += s[i][g];
       }
       lsum[g] = lsum[g] * alpha + add;
 #pragma unroll
       for (int c = 0; c < 8; ++c) o[g][c] *= alpha;
+    }
+    if (t_limit < B) {
+      // Slots past the context may hold anything (NaN patterns included): clear
+      // their V rows so that a zero weight cannot turn them into NaN.
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        if (i * TPI + row >= t_limit) vc[i] = v4u{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -261,15 +284,11 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(p[i][g], vf[c], o[g][c]);
+        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(s[i][g], vf[c], o[g][c]);
     }
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < NI; ++i) {
-        kc[i] = kn[i];
-        vc[i] = vn[i];
-      }
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) load_v(it + 1, vc);
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // ---- merge the NP states of the workgroup through LDS ----

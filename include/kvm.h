@@ -89,6 +89,14 @@ typedef struct {
                                     checked for duplicates.  NULL skips those
                                     checks: ids are then the caller's promise. */
   const int32_t* k;              /* host,   [n_req] */
+  const int32_t* start;          /* host,   [n_req] or NULL (= all zero): first
+                                    token to move.  With start[r] > 0 only tokens
+                                    [start[r], k[r]) are moved; they keep their
+                                    logical index, so entry j of the table still
+                                    covers tokens [j*B, j*B+B).  This is the unit
+                                    of a multi-round live migration, where an
+                                    earlier round has already moved [0,start).
+                                    0 <= start[r] <= k[r]. */
 } kvm_batch;
 
 /* ---- closed-form sizes (host, pure) -------------------------------------
@@ -97,8 +105,9 @@ typedef struct {
  * NULL or inconsistent layout. */
 int64_t kvm_bytes_per_token(const kvm_layout* layout);
 int64_t kvm_block_bytes(const kvm_layout* layout); /* block_tokens * bytes_per_token */
-/* Sum over the batch of k[r] * bytes_per_token: the size of the staging buffer
- * written by kvm_pack and read by kvm_unpack.  Exactly linear in k, no padding. */
+/* Sum over the batch of (k[r] - start[r]) * bytes_per_token: the size of the
+ * staging buffer written by kvm_pack and read by kvm_unpack.  Exactly linear in
+ * the number of tokens, no padding. */
 int64_t kvm_staging_bytes(const kvm_layout* layout, const kvm_batch* batch);
 
 /* Fill `out` with the canonical dense layout
@@ -118,8 +127,15 @@ int64_t kvm_pool_span_bytes(const kvm_layout* layout, int64_t n_blocks);
  * the cache being append-only, so a prefix [0,k) is a valid unit of transfer).
  *
  * Staging ("wire") format, shared by kvm_pack and kvm_unpack: requests in
- * batch order, each as [layer][kv][head][token t < k[r]][dim], 16-bit elements,
- * no padding; request r starts at byte (sum_{r'<r} k[r']) * bytes_per_token.
+ * batch order, each as [layer][kv][head][token start[r] <= t < k[r]][dim], 16-bit
+ * elements, no padding; request r starts at byte
+ * (sum_{r'<r} (k[r'] - start[r'])) * bytes_per_token.
+ *
+ * Token ranges (Sec. "Background & Related Work": live migration copies the
+ * cache of the legacy tokens while new tokens are still being decoded, which the
+ * append-only cache allows): with batch.start set, each call moves only
+ * [start[r], k[r]); moving [0,a) and later [a,b) leaves the destination exactly
+ * as moving [0,b) at once.
  */
 
 /* Gather: staging[...] = src pool contents of tokens [0,k[r]) of each request.
@@ -143,8 +159,8 @@ int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* d
  * The source pool is never written (Sec. "Adaptive Request Migration",
  * "Boundary Profiling": source memory stays allocated until the transfer is
  * complete; releasing it is the caller's later step).
- * KVM_EINVAL additionally when: n_req or any k[r] differs between the two
- * batches; the layouts differ in anything but strides; src and dst are the
+ * KVM_EINVAL additionally when: n_req or any k[r] or start[r] differs between the
+ * two batches; the layouts differ in anything but strides; src and dst are the
  * same allocation region and a written dst block id is also a read src id. */
 int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* dst,
                 const kvm_batch* dst_reqs, void* hip_stream);
@@ -190,6 +206,37 @@ int kvm_freelist_free(kvm_freelist* fl, int32_t n, const int32_t* ids);
  * tables).  KVM_EINVAL (and no change) if an id is out of range, not free, or
  * repeated in `ids`. */
 int kvm_freelist_reserve(kvm_freelist* fl, int32_t n, const int32_t* ids);
+
+/* ---- hybrid-migration divider (host, integers only) -----------------------
+ * Sec. "Adaptive Request Migration", "Hybrid Migration" and "Global Consensus":
+ * every request to be migrated is put into one of two classes, transferred as KV
+ * cache (k = len for kvm_migrate) or transferred as tokens and re-prefilled on the
+ * destination (k = 0), so that the KV bytes sent over each link stay within the
+ * link's communication boundary and the tokens to prefill on each destination
+ * instance stay within its computation boundary: a two-bin packing solved
+ * greedily.  All pending moves of the whole system are given in one list, in an
+ * order every instance agrees on; the function is deterministic, so every
+ * instance that runs it reaches the same division.
+ *
+ * Moves are taken in list order.  KVM_FIRST_FIT tries the KV class first, then
+ * the token class.  KVM_BEST_FIT picks, among the classes that still have room,
+ * the one whose bin is left with the smaller free fraction of its boundary
+ * (ties: KV).  A move that fits neither bin is KVM_CLASS_DEFER (left for a later
+ * epoch).  A boundary of 0 closes the bin; moves with kv_bytes = 0 or tokens = 0
+ * cost nothing in that bin.
+ * KVM_EINVAL: NULL pointers, negative sizes or boundaries, link / dst out of
+ * range, unknown policy. */
+typedef struct {
+  int32_t link;     /* index into comm_boundary: the link the KV bytes would cross */
+  int32_t dst;      /* index into comp_boundary: the instance that would prefill */
+  int64_t kv_bytes; /* size of the request's KV cache (len * bytes_per_token) */
+  int64_t tokens;   /* tokens to prefill if sent as tokens */
+} kvm_move;
+typedef enum { KVM_CLASS_KV = 0, KVM_CLASS_TOKENS = 1, KVM_CLASS_DEFER = 2 } kvm_move_class;
+typedef enum { KVM_FIRST_FIT = 0, KVM_BEST_FIT = 1 } kvm_divide_policy;
+int kvm_divide_moves(const kvm_move* moves, int32_t n_moves, const int64_t* comm_boundary,
+                     int32_t n_links, const int64_t* comp_boundary, int32_t n_instances,
+                     int32_t policy, int32_t* out_class);
 
 /* ---- diagnostics ---------------------------------------------------------- */
 const char* kvm_strerror(int status);

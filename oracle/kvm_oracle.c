@@ -46,17 +46,21 @@ static int64_t pool_index(const int64_t* st, int l, int kv, int64_t b, int h, in
 int64_t orc_bytes_per_token(int L, int H, int D) { return (int64_t)L * 2 * H * D * 2; }
 
 /* Fused migration: logical token t of request r keeps its logical index and
- * changes only its physical block.  Layers [l_begin, l_end) are processed so
- * that a caller may hand disjoint layer ranges to several threads. */
+ * changes only its physical block.  Tokens [start[r], k[r]) are moved: start = 0
+ * is a whole prefix; start > 0 is one round of a live migration in which an
+ * earlier round moved [0,start) (the cache is append-only, so that part is still
+ * valid: Sec. "Background & Related Work" on live migration, Sec. "Motivation",
+ * Finding 4).  Layers [l_begin, l_end) are processed so that a caller may hand
+ * disjoint layer ranges to several threads. */
 void orc_migrate(const uint16_t* src, const int64_t* src_st, uint16_t* dst, const int64_t* dst_st,
                  int L, int H, int D, int B, int n_req, const int32_t* src_off,
                  const int32_t* src_blocks, const int32_t* dst_off, const int32_t* dst_blocks,
-                 const int32_t* k, int l_begin, int l_end) {
+                 const int32_t* k, const int32_t* start, int l_begin, int l_end) {
   (void)L;
   for (int r = 0; r < n_req; ++r)
     for (int l = l_begin; l < l_end; ++l)
       for (int kv = 0; kv < 2; ++kv)
-        for (int t = 0; t < k[r]; ++t) {
+        for (int t = start[r]; t < k[r]; ++t) {
           int64_t bs = src_blocks[src_off[r] + t / B];
           int64_t bd = dst_blocks[dst_off[r] + t / B];
           for (int h = 0; h < H; ++h)
@@ -66,47 +70,49 @@ void orc_migrate(const uint16_t* src, const int64_t* src_st, uint16_t* dst, cons
         }
 }
 
-/* Staging index of (request r, layer l, kv, head h, token t, dim d): requests
- * concatenated in batch order, each [layer][kv][head][token][dim] over exactly
- * its k[r] tokens. */
-static int64_t stage_index(int64_t req_base, int H, int D, int kr, int l, int kv, int h, int t,
+/* Staging index of (request r, layer l, kv, head h, moved token number u, dim
+ * d): requests concatenated in batch order, each [layer][kv][head][token][dim]
+ * over exactly its n = k[r] - start[r] moved tokens, u = t - start[r]. */
+static int64_t stage_index(int64_t req_base, int H, int D, int n, int l, int kv, int h, int u,
                            int d) {
-  return req_base + ((((int64_t)l * 2 + kv) * H + h) * kr + t) * D + d;
+  return req_base + ((((int64_t)l * 2 + kv) * H + h) * n + u) * D + d;
 }
 
 void orc_pack(const uint16_t* src, const int64_t* src_st, uint16_t* stage, int L, int H, int D,
               int B, int n_req, const int32_t* off, const int32_t* blocks, const int32_t* k,
-              int l_begin, int l_end) {
+              const int32_t* start, int l_begin, int l_end) {
   int64_t req_base = 0;
   for (int r = 0; r < n_req; ++r) {
+    int n = k[r] - start[r];
     for (int l = l_begin; l < l_end; ++l)
       for (int kv = 0; kv < 2; ++kv)
         for (int h = 0; h < H; ++h)
-          for (int t = 0; t < k[r]; ++t) {
+          for (int t = start[r]; t < k[r]; ++t) {
             int64_t b = blocks[off[r] + t / B];
             for (int d = 0; d < D; ++d)
-              stage[stage_index(req_base, H, D, k[r], l, kv, h, t, d)] =
+              stage[stage_index(req_base, H, D, n, l, kv, h, t - start[r], d)] =
                   src[pool_index(src_st, l, kv, b, h, t % B, d)];
           }
-    req_base += (int64_t)k[r] * L * 2 * H * D;
+    req_base += (int64_t)n * L * 2 * H * D;
   }
 }
 
 void orc_unpack(const uint16_t* stage, uint16_t* dst, const int64_t* dst_st, int L, int H, int D,
                 int B, int n_req, const int32_t* off, const int32_t* blocks, const int32_t* k,
-                int l_begin, int l_end) {
+                const int32_t* start, int l_begin, int l_end) {
   int64_t req_base = 0;
   for (int r = 0; r < n_req; ++r) {
+    int n = k[r] - start[r];
     for (int l = l_begin; l < l_end; ++l)
       for (int kv = 0; kv < 2; ++kv)
         for (int h = 0; h < H; ++h)
-          for (int t = 0; t < k[r]; ++t) {
+          for (int t = start[r]; t < k[r]; ++t) {
             int64_t b = blocks[off[r] + t / B];
             for (int d = 0; d < D; ++d)
               dst[pool_index(dst_st, l, kv, b, h, t % B, d)] =
-                  stage[stage_index(req_base, H, D, k[r], l, kv, h, t, d)];
+                  stage[stage_index(req_base, H, D, n, l, kv, h, t - start[r], d)];
           }
-    req_base += (int64_t)k[r] * L * 2 * H * D;
+    req_base += (int64_t)n * L * 2 * H * D;
   }
 }
 

@@ -48,13 +48,13 @@ def _load():
         lib.orc_bytes_per_token.argtypes = [_INT, _INT, _INT]
         lib.orc_migrate.restype = None
         lib.orc_migrate.argtypes = [_U16P, _I64P, _U16P, _I64P, _INT, _INT, _INT, _INT, _INT,
-                                    _I32P, _I32P, _I32P, _I32P, _I32P, _INT, _INT]
+                                    _I32P, _I32P, _I32P, _I32P, _I32P, _I32P, _INT, _INT]
         lib.orc_pack.restype = None
         lib.orc_pack.argtypes = [_U16P, _I64P, _U16P, _INT, _INT, _INT, _INT, _INT,
-                                 _I32P, _I32P, _I32P, _INT, _INT]
+                                 _I32P, _I32P, _I32P, _I32P, _INT, _INT]
         lib.orc_unpack.restype = None
         lib.orc_unpack.argtypes = [_U16P, _U16P, _I64P, _INT, _INT, _INT, _INT, _INT,
-                                   _I32P, _I32P, _I32P, _INT, _INT]
+                                   _I32P, _I32P, _I32P, _I32P, _INT, _INT]
         lib.orc_widen.restype = ctypes.c_double
         lib.orc_widen.argtypes = [ctypes.c_uint16, _INT]
         lib.orc_paged_decode.restype = None
@@ -108,9 +108,16 @@ def _check_tables(pool_elems, st, L, H, D, B, off, blocks, k):
             assert top < pool_elems, "block id beyond pool"
 
 
+def _start(start, k):
+    st = np.zeros(len(k), dtype=np.int32) if start is None else _i32(start)
+    assert len(st) == len(k) and (st >= 0).all() and (st <= k).all()
+    return st
+
+
 def migrate(src, src_st, dst, dst_st, L, H, D, B, src_off, src_blocks, dst_off, dst_blocks, k,
-            layers=None):
-    """dst <- tokens [0,k[r]) of every request, in place; src is not written."""
+            layers=None, start=None):
+    """dst <- tokens [start[r],k[r]) of every request (start defaults to 0), in
+    place; src is not written."""
     src_off, src_blocks = _i32(src_off), _i32(src_blocks)
     dst_off, dst_blocks, k = _i32(dst_off), _i32(dst_blocks), _i32(k)
     src_st, dst_st = _st(src_st), _st(dst_st)
@@ -118,32 +125,35 @@ def migrate(src, src_st, dst, dst_st, L, H, D, B, src_off, src_blocks, dst_off, 
     _check_tables(dst.size, dst_st, L, H, D, B, dst_off, dst_blocks, k)
     lb, le = layers if layers is not None else (0, L)
     _load().orc_migrate(src, src_st, dst, dst_st, L, H, D, B, len(k), src_off, src_blocks,
-                        dst_off, dst_blocks, k, lb, le)
+                        dst_off, dst_blocks, k, _start(start, k), lb, le)
 
 
-def staging_elems(L, H, D, k):
-    return int(np.sum(np.asarray(k, dtype=np.int64))) * L * 2 * H * D
+def staging_elems(L, H, D, k, start=None):
+    n = np.asarray(k, dtype=np.int64) - (0 if start is None else np.asarray(start, dtype=np.int64))
+    return int(np.sum(n)) * L * 2 * H * D
 
 
-def pack(src, src_st, L, H, D, B, off, blocks, k, stage=None, layers=None):
-    """Returns the staging buffer (uint16) of tokens [0,k[r]) of every request."""
+def pack(src, src_st, L, H, D, B, off, blocks, k, stage=None, layers=None, start=None):
+    """Returns the staging buffer (uint16) of tokens [start[r],k[r]) of every request."""
     off, blocks, k, src_st = _i32(off), _i32(blocks), _i32(k), _st(src_st)
     _check_tables(src.size, src_st, L, H, D, B, off, blocks, k)
+    st = _start(start, k)
     if stage is None:
-        stage = np.zeros(staging_elems(L, H, D, k), dtype=np.uint16)
-    assert stage.size >= staging_elems(L, H, D, k)
+        stage = np.zeros(staging_elems(L, H, D, k, st), dtype=np.uint16)
+    assert stage.size >= staging_elems(L, H, D, k, st)
     lb, le = layers if layers is not None else (0, L)
-    _load().orc_pack(src, src_st, stage, L, H, D, B, len(k), off, blocks, k, lb, le)
+    _load().orc_pack(src, src_st, stage, L, H, D, B, len(k), off, blocks, k, st, lb, le)
     return stage
 
 
-def unpack(stage, dst, dst_st, L, H, D, B, off, blocks, k, layers=None):
+def unpack(stage, dst, dst_st, L, H, D, B, off, blocks, k, layers=None, start=None):
     """Scatter a staging buffer into dst's blocks, in place."""
     off, blocks, k, dst_st = _i32(off), _i32(blocks), _i32(k), _st(dst_st)
     _check_tables(dst.size, dst_st, L, H, D, B, off, blocks, k)
-    assert stage.size >= staging_elems(L, H, D, k)
+    st = _start(start, k)
+    assert stage.size >= staging_elems(L, H, D, k, st)
     lb, le = layers if layers is not None else (0, L)
-    _load().orc_unpack(stage, dst, dst_st, L, H, D, B, len(k), off, blocks, k, lb, le)
+    _load().orc_unpack(stage, dst, dst_st, L, H, D, B, len(k), off, blocks, k, st, lb, le)
 
 
 def widen(bits, dtype):
@@ -207,3 +217,40 @@ class FreeList:
                 raise ValueError("id %d not allocated" % b)
         for b in ids:
             self.free[b] = True
+
+
+CLASS_KV, CLASS_TOKENS, CLASS_DEFER = 0, 1, 2
+
+
+def divide_moves(moves, comm_boundary, comp_boundary, policy="first_fit"):
+    """Hybrid-migration divider (Sec. "Adaptive Request Migration", "Hybrid
+    Migration" / "Global Consensus"): each pending move, in list order, goes to the
+    KV-transfer class if its bytes still fit the link's communication boundary, to
+    the token-transfer class if its tokens still fit the destination's computation
+    boundary, else it is deferred.  `moves`: (link, dst, kv_bytes, tokens).
+    first_fit tries KV first; best_fit takes the class whose bin keeps the smaller
+    free fraction of its boundary (a bin with boundary 0 counts as fraction 0; ties
+    go to KV).  Returns the list of classes."""
+    from fractions import Fraction
+    link_left = [int(c) for c in comm_boundary]
+    inst_left = [int(c) for c in comp_boundary]
+    out = []
+    for link, dst, kv_bytes, tokens in moves:
+        fits_kv = kv_bytes <= link_left[link]
+        fits_tok = tokens <= inst_left[dst]
+        if fits_kv and fits_tok and policy == "best_fit":
+            f_kv = Fraction(link_left[link] - kv_bytes, comm_boundary[link]) if comm_boundary[link] else 0
+            f_tok = Fraction(inst_left[dst] - tokens, comp_boundary[dst]) if comp_boundary[dst] else 0
+            cls = CLASS_KV if f_kv <= f_tok else CLASS_TOKENS
+        elif fits_kv:
+            cls = CLASS_KV
+        elif fits_tok:
+            cls = CLASS_TOKENS
+        else:
+            cls = CLASS_DEFER
+        if cls == CLASS_KV:
+            link_left[link] -= kv_bytes
+        elif cls == CLASS_TOKENS:
+            inst_left[dst] -= tokens
+        out.append(cls)
+    return out

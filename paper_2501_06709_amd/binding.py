@@ -42,7 +42,7 @@ class kvm_pool(ctypes.Structure):
 class kvm_batch(ctypes.Structure):
     _fields_ = [("n_req", ctypes.c_int32), ("bt_offsets", ctypes.c_void_p),
                 ("bt_blocks_dev", ctypes.c_void_p), ("bt_blocks_host", ctypes.c_void_p),
-                ("k", ctypes.c_void_p)]
+                ("k", ctypes.c_void_p), ("start", ctypes.c_void_p)]
 
 
 _lib = None
@@ -90,6 +90,8 @@ def lib():
         L.kvm_freelist_free.argtypes = [VP, I32, VP]
         L.kvm_freelist_reserve.restype = ctypes.c_int
         L.kvm_freelist_reserve.argtypes = [VP, I32, VP]
+        L.kvm_divide_moves.restype = ctypes.c_int
+        L.kvm_divide_moves.argtypes = [VP, I32, VP, I32, VP, I32, I32, VP]
         L.kvm_strerror.restype = ctypes.c_char_p
         L.kvm_strerror.argtypes = [ctypes.c_int]
         L.kvm_last_error.restype = ctypes.c_char_p
@@ -158,17 +160,21 @@ class Pool:
 class Batch:
     """CSR block tables of a batch.  `blocks_dev` is a device int32 buffer with
     the same ids as `blocks` (host); `host_ids=False` withholds the host copy so
-    the library skips its id checks."""
+    the library skips its id checks; `start` (optional) makes every call move only
+    tokens [start[r], k[r])."""
 
-    def __init__(self, offsets, blocks, k, blocks_dev, host_ids=True):
+    def __init__(self, offsets, blocks, k, blocks_dev, host_ids=True, start=None):
         self.offsets = np.ascontiguousarray(offsets, dtype=np.int32)
         self.blocks = np.ascontiguousarray(blocks, dtype=np.int32)
         self.k = np.ascontiguousarray(k, dtype=np.int32)
+        self.start = None if start is None else np.ascontiguousarray(start, dtype=np.int32)
+        assert self.start is None or len(self.start) == len(self.k)
         self.blocks_dev = blocks_dev
         self.n_req = len(self.k)
         assert len(self.offsets) == self.n_req + 1
         self.c = kvm_batch(self.n_req, self.offsets.ctypes.data, _devptr(blocks_dev),
-                           self.blocks.ctypes.data if host_ids else None, self.k.ctypes.data)
+                           self.blocks.ctypes.data if host_ids else None, self.k.ctypes.data,
+                           None if self.start is None else self.start.ctypes.data)
 
 
 def kvm_staging_bytes(layout, batch):
@@ -205,6 +211,25 @@ def kvm_paged_decode(pool, reqs, q, out, out_is_f32=True, scale=0.0, workspace=N
     return _check(lib().kvm_paged_decode(ctypes.byref(pool.c), ctypes.byref(reqs.c), _devptr(q),
                                          _devptr(out), 1 if out_is_f32 else 0, scale,
                                          _devptr(workspace), workspace_bytes or 0, _stream(stream)))
+
+
+KVM_CLASS_KV, KVM_CLASS_TOKENS, KVM_CLASS_DEFER = 0, 1, 2
+KVM_FIRST_FIT, KVM_BEST_FIT = 0, 1
+MOVE_DTYPE = np.dtype([("link", np.int32), ("dst", np.int32), ("kv_bytes", np.int64),
+                       ("tokens", np.int64)])
+
+
+def kvm_divide_moves(moves, comm_boundary, comp_boundary, policy=KVM_FIRST_FIT):
+    """moves: sequence of (link, dst, kv_bytes, tokens); returns int32 classes."""
+    mv = np.array([tuple(m) for m in moves], dtype=MOVE_DTYPE) if len(moves) else np.zeros(0, MOVE_DTYPE)
+    comm = np.ascontiguousarray(comm_boundary, dtype=np.int64)
+    comp = np.ascontiguousarray(comp_boundary, dtype=np.int64)
+    out = np.full(len(mv), -1, dtype=np.int32)
+    _check(lib().kvm_divide_moves(mv.ctypes.data if len(mv) else None, len(mv),
+                                  comm.ctypes.data if len(comm) else None, len(comm),
+                                  comp.ctypes.data if len(comp) else None, len(comp),
+                                  int(policy), out.ctypes.data if len(mv) else None))
+    return out
 
 
 def kvm_set_option(name, value):

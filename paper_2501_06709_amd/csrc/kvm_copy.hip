@@ -44,8 +44,10 @@ struct PoolSide {
 struct CopyReq {
   int32_t src_bt;      // first table entry of the request on the source side
   int32_t dst_bt;      // ... on the destination side
-  int32_t k;           // tokens to move
-  int32_t first_item;  // index of the request's first block among the launch's items
+  int32_t k;           // tokens [start, k) are moved
+  int32_t start;
+  int32_t first_item;  // index of the request's first moved block among the launch's items
+  int32_t pad;
   int64_t stage_vec;   // staging offset of the request in 16-byte vectors
 };
 
@@ -131,11 +133,14 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
       const int t = r + s;
       if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
     }
-    j = (int32_t)item - a.req[r].first_item;  // logical block of the request
+    j = (int32_t)item - a.req[r].first_item;  // block of the request, counted from its first moved one
   }
   const CopyReq rq = a.req[r];
-  const int32_t rem_tokens = rq.k - j * a.B;
-  const uint32_t ns = rem_tokens < a.B ? (uint32_t)rem_tokens : (uint32_t)a.B;  // slots to move
+  j += rq.start / a.B;                          // logical block of the request
+  // slots [s0, s1) of this block hold tokens of [start, k)
+  const int32_t lo = rq.start - j * a.B, hi = rq.k - j * a.B;
+  const uint32_t s0 = lo > 0 ? (uint32_t)lo : 0u;
+  const uint32_t ns = (hi < a.B ? (uint32_t)hi : (uint32_t)a.B) - s0;  // slots to move
   const uint32_t layer = plane >> 1, kv = plane & 1;
 
   const char* sbase = nullptr;
@@ -143,12 +148,14 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   bool dense = ns == (uint32_t)a.B;
   if (MODE != kUnpack) {
     const int64_t blk = a.src.bt[rq.src_bt + j];
-    sbase = a.src.base + layer * a.src.stride_layer + kv * a.src.stride_kv + blk * a.src.stride_block;
+    sbase = a.src.base + layer * a.src.stride_layer + kv * a.src.stride_kv + blk * a.src.stride_block +
+            (uint64_t)s0 * a.src.stride_slot;
     dense = dense && a.src.dense;
   }
   if (MODE != kPack) {
     const int64_t blk = a.dst.bt[rq.dst_bt + j];
-    dbase = a.dst.base + layer * a.dst.stride_layer + kv * a.dst.stride_kv + blk * a.dst.stride_block;
+    dbase = a.dst.base + layer * a.dst.stride_layer + kv * a.dst.stride_kv + blk * a.dst.stride_block +
+            (uint64_t)s0 * a.dst.stride_slot;
     dense = dense && a.dst.dense;
   }
   const uint32_t per_head = ns * a.DV;          // vectors per head in this item
@@ -176,12 +183,14 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   }
 
   // general path: vector index -> (head, slot, vector-in-row)
-  char* stage_plane = nullptr;  // staging address of (request, plane, head 0, token j*B)
+  char* stage_plane = nullptr;  // staging address of (request, plane, head 0, token j*B + s0)
   uint64_t stage_head = 0;      // bytes between heads in staging
   if (MODE != kMigrate) {
-    stage_head = (uint64_t)rq.k * a.DV * 16u;
-    stage_plane = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)plane * a.H * rq.k * a.DV +
-                             (uint64_t)j * a.B * a.DV) * 16u;
+    const uint64_t n_tok = (uint64_t)(rq.k - rq.start);             // tokens of the request in staging
+    const uint64_t tok0 = (uint64_t)(j * a.B + (int32_t)s0 - rq.start);  // first of them in this item
+    stage_head = n_tok * a.DV * 16u;
+    stage_plane = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)plane * a.H * n_tok * a.DV +
+                             tok0 * a.DV) * 16u;
   }
   uint32_t soff[U], doff[U];
   uint64_t shead[U];
@@ -296,17 +305,19 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
     a.n_items = 0;
     const int64_t max_items = (int64_t)0x7fffffff / ((int64_t)a.n_planes * a.n_chunks);
     while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
-      if (view.nb[r] > max_items)
+      const int32_t items_r = view.nb[r] - view.jb[r];
+      if (items_r > max_items)
         return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
-      if ((int64_t)a.n_items + view.nb[r] > max_items) break;
+      if ((int64_t)a.n_items + items_r > max_items) break;
       CopyReq& q = a.req[a.n_req++];
       q.src_bt = sv.bt_off[r];
       q.dst_bt = dv.bt_off[r];
       q.k = view.k[r];
+      q.start = view.start[r];
       q.first_item = a.n_items;
       q.stage_vec = stage_vec;
-      a.n_items += view.nb[r];
-      stage_vec += (int64_t)view.k[r] * bpt_vec;
+      a.n_items += items_r;
+      stage_vec += (int64_t)(view.k[r] - view.start[r]) * bpt_vec;
       ++r;
     }
     if (a.n_items == 0) continue;  // only k = 0 requests in this group
@@ -367,8 +378,11 @@ int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* 
   if (!same_shape(src->layout, dst->layout))
     return fail(KVM_EINVAL, "kvm_migrate: src and dst layouts differ in more than strides");
   if (sv.n_req != dv.n_req) return fail(KVM_EINVAL, "kvm_migrate: n_req differs between src and dst");
-  for (int r = 0; r < sv.n_req; ++r)
+  for (int r = 0; r < sv.n_req; ++r) {
     if (sv.k[r] != dv.k[r]) return fail(KVM_EINVAL, "kvm_migrate: k differs between src and dst");
+    if (sv.start[r] != dv.start[r])
+      return fail(KVM_EINVAL, "kvm_migrate: start differs between src and dst");
+  }
   // Overlapping memory: only the same pool with disjoint block sets is allowed.
   const char* s0 = (const char*)src->base;
   const char* d0 = (const char*)dst->base;
@@ -384,12 +398,12 @@ int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* 
       return fail(KVM_EINVAL, "kvm_migrate: in-pool migration needs host block ids on both sides");
     std::vector<uint64_t> wr((size_t)ceil_div(dst->n_blocks, 64), 0);
     for (int r = 0; r < dv.n_req; ++r)
-      for (int j = 0; j < dv.nb[r]; ++j) {
+      for (int j = dv.jb[r]; j < dv.nb[r]; ++j) {
         const int32_t id = dst_reqs->bt_blocks_host[dv.bt_off[r] + j];
         wr[(size_t)id >> 6] |= 1ull << (id & 63);
       }
     for (int r = 0; r < sv.n_req; ++r)
-      for (int j = 0; j < sv.nb[r]; ++j) {
+      for (int j = sv.jb[r]; j < sv.nb[r]; ++j) {
         const int32_t id = src_reqs->bt_blocks_host[sv.bt_off[r] + j];
         if (wr[(size_t)id >> 6] & (1ull << (id & 63)))
           return fail(KVM_EINVAL, "kvm_migrate: a block is both read and written");

@@ -431,6 +431,8 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
   BatchView v;
   int rc = validate_side("kvm_paged_decode", pool, reqs, false, &v);
   if (rc) return rc;
+  for (int r = 0; r < v.n_req; ++r)
+    if (v.start[r] != 0) return fail(KVM_EINVAL, "kvm_paged_decode: reqs->start must be NULL or zero");
   if (v.n_req == 0 || v.total_blocks == 0) return KVM_OK;
   if (!q_dev || !out_dev) return fail(KVM_EINVAL, "kvm_paged_decode: q_dev or out_dev is NULL");
   if ((uintptr_t)q_dev % 16 || (uintptr_t)out_dev % 4)

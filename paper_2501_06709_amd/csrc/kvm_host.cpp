@@ -63,6 +63,8 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
   out->n_req = batch->n_req;
   out->bt_off.assign(batch->n_req, 0);
   out->k.assign(batch->n_req, 0);
+  out->start.assign(batch->n_req, 0);
+  out->jb.assign(batch->n_req, 0);
   out->nb.assign(batch->n_req, 0);
   out->total_tokens = out->total_blocks = 0;
   if (batch->n_req == 0) return KVM_OK;
@@ -79,11 +81,18 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
                (long long)((hi - lo) * B));
       return fail(KVM_EINVAL, w + buf);
     }
+    const int64_t st = batch->start ? batch->start[r] : 0;
+    if (st < 0 || st > k) {
+      snprintf(buf, sizeof buf, ": start[%d]=%lld outside [0, k=%lld]", r, (long long)st, (long long)k);
+      return fail(KVM_EINVAL, w + buf);
+    }
     out->bt_off[r] = (int32_t)lo;
     out->k[r] = (int32_t)k;
-    out->nb[r] = (int32_t)ceil_div(k, B);
-    out->total_tokens += k;
-    out->total_blocks += out->nb[r];
+    out->start[r] = (int32_t)st;
+    out->jb[r] = (int32_t)(st / B);
+    out->nb[r] = k > st ? (int32_t)ceil_div(k, B) : out->jb[r];
+    out->total_tokens += k - st;
+    out->total_blocks += out->nb[r] - out->jb[r];
   }
   if (out->total_blocks > 0 && !batch->bt_blocks_dev)
     return fail(KVM_EINVAL, w + ": bt_blocks_dev is NULL");
@@ -91,7 +100,7 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
     std::vector<uint64_t> seen;
     if (writing) seen.assign((size_t)ceil_div(pool->n_blocks, 64), 0);
     for (int r = 0; r < batch->n_req; ++r)
-      for (int j = 0; j < out->nb[r]; ++j) {
+      for (int j = out->jb[r]; j < out->nb[r]; ++j) {
         const int64_t id = batch->bt_blocks_host[out->bt_off[r] + j];
         char buf[96];
         if (id < 0 || id >= pool->n_blocks) {
@@ -135,8 +144,9 @@ int64_t kvm_staging_bytes(const kvm_layout* l, const kvm_batch* b) {
   if (bpt < 0 || !b || b->n_req < 0 || (b->n_req > 0 && !b->k)) return -1;
   int64_t tokens = 0;
   for (int r = 0; r < b->n_req; ++r) {
-    if (b->k[r] < 0) return -1;
-    tokens += b->k[r];
+    const int64_t st = b->start ? b->start[r] : 0;
+    if (b->k[r] < 0 || st < 0 || st > b->k[r]) return -1;
+    tokens += b->k[r] - st;
   }
   return tokens * bpt;
 }
@@ -256,6 +266,54 @@ int kvm_freelist_reserve(kvm_freelist* fl, int32_t n, const int32_t* ids) {
     return fail(KVM_EINVAL, "kvm_freelist_reserve: id out of range, not free, or repeated");
   }
   fl->n_free -= n;
+  return KVM_OK;
+}
+
+int kvm_divide_moves(const kvm_move* moves, int32_t n_moves, const int64_t* comm_boundary,
+                     int32_t n_links, const int64_t* comp_boundary, int32_t n_instances,
+                     int32_t policy, int32_t* out_class) {
+  if (n_moves < 0 || n_links < 0 || n_instances < 0)
+    return fail(KVM_EINVAL, "kvm_divide_moves: negative count");
+  if ((n_moves > 0 && (!moves || !out_class)) || (n_links > 0 && !comm_boundary) ||
+      (n_instances > 0 && !comp_boundary))
+    return fail(KVM_EINVAL, "kvm_divide_moves: NULL pointer");
+  if (policy != KVM_FIRST_FIT && policy != KVM_BEST_FIT)
+    return fail(KVM_EINVAL, "kvm_divide_moves: unknown policy");
+  for (int32_t l = 0; l < n_links; ++l)
+    if (comm_boundary[l] < 0) return fail(KVM_EINVAL, "kvm_divide_moves: negative boundary");
+  for (int32_t j = 0; j < n_instances; ++j)
+    if (comp_boundary[j] < 0) return fail(KVM_EINVAL, "kvm_divide_moves: negative boundary");
+  for (int32_t i = 0; i < n_moves; ++i) {
+    const kvm_move& mv = moves[i];
+    if (mv.link < 0 || mv.link >= n_links || mv.dst < 0 || mv.dst >= n_instances)
+      return fail(KVM_EINVAL, "kvm_divide_moves: link or dst out of range");
+    if (mv.kv_bytes < 0 || mv.tokens < 0) return fail(KVM_EINVAL, "kvm_divide_moves: negative size");
+  }
+  std::vector<int64_t> link_left(comm_boundary, comm_boundary + n_links);
+  std::vector<int64_t> inst_left(comp_boundary, comp_boundary + n_instances);
+  for (int32_t i = 0; i < n_moves; ++i) {
+    const kvm_move& mv = moves[i];
+    const bool fits_kv = mv.kv_bytes <= link_left[mv.link];
+    const bool fits_tok = mv.tokens <= inst_left[mv.dst];
+    int cls = KVM_CLASS_DEFER;
+    if (fits_kv && fits_tok && policy == KVM_BEST_FIT) {
+      // compare free fractions (left - size) / boundary without division:
+      // a/b <= c/d  <=>  a*d <= c*b for positive b, d; an empty bin (boundary 0,
+      // size 0) counts as fraction 0
+      const __int128 a = link_left[mv.link] - mv.kv_bytes, b = comm_boundary[mv.link];
+      const __int128 c = inst_left[mv.dst] - mv.tokens, d = comp_boundary[mv.dst];
+      const __int128 lhs = b == 0 ? 0 : a * (d == 0 ? 1 : d);
+      const __int128 rhs = d == 0 ? 0 : c * (b == 0 ? 1 : b);
+      cls = lhs <= rhs ? KVM_CLASS_KV : KVM_CLASS_TOKENS;
+    } else if (fits_kv) {
+      cls = KVM_CLASS_KV;
+    } else if (fits_tok) {
+      cls = KVM_CLASS_TOKENS;
+    }
+    if (cls == KVM_CLASS_KV) link_left[mv.link] -= mv.kv_bytes;
+    if (cls == KVM_CLASS_TOKENS) inst_left[mv.dst] -= mv.tokens;
+    out_class[i] = cls;
+  }
   return KVM_OK;
 }
 

@@ -25,9 +25,11 @@ struct BatchView {
   int n_req = 0;
   std::vector<int32_t> bt_off;  // first table entry of request r
   std::vector<int32_t> k;
-  std::vector<int32_t> nb;      // ceil(k / B)
-  int64_t total_tokens = 0;
-  int64_t total_blocks = 0;
+  std::vector<int32_t> start;   // first token moved (0 without a range)
+  std::vector<int32_t> jb;      // first block that holds a moved token: start / B
+  std::vector<int32_t> nb;      // one past the last such block: ceil(k / B), or jb if k == start
+  int64_t total_tokens = 0;     // sum of k - start
+  int64_t total_blocks = 0;     // sum of nb - jb
 };
 
 // Checks pool + batch (pointers, alignment, layout, offsets, k range, id range).

@@ -39,7 +39,7 @@ def dev_table(blk):
 class Side:
     """One pool on host (uint16 array) and device, with its tables."""
 
-    def __init__(self, m, n_blocks, host, tables, k, strides=None, host_ids=True):
+    def __init__(self, m, n_blocks, host, tables, k, strides=None, host_ids=True, start=None):
         self.m, self.n_blocks = m, n_blocks
         self.st = np.asarray(wl.canonical_strides(m, n_blocks) if strides is None else strides,
                              dtype=np.int64)
@@ -51,7 +51,9 @@ class Side:
         self.off, self.blk = csr(tables)
         self.k = np.asarray(k, dtype=np.int32)
         self.blk_dev = dev_table(self.blk)
-        self.batch = kvm.Batch(self.off, self.blk, self.k, self.blk_dev, host_ids=host_ids)
+        self.start = None if start is None else np.asarray(start, dtype=np.int32)
+        self.batch = kvm.Batch(self.off, self.blk, self.k, self.blk_dev, host_ids=host_ids,
+                               start=self.start)
 
 
 def random_bits(rng, n):
@@ -70,7 +72,7 @@ def tables_from_perm(rng, n_blocks, counts):
 
 
 def make_pair(m, n_src, n_dst, lens, ks, seed, src_strides=None, dst_strides=None, finite=False,
-              host_ids=True):
+              host_ids=True, start=None):
     """Source and destination sides of a migration with random placement."""
     rng = np.random.default_rng(seed)
     B = m.B
@@ -84,8 +86,8 @@ def make_pair(m, n_src, n_dst, lens, ks, seed, src_strides=None, dst_strides=Non
     else:
         h_src = random_bits(rng, wl.pool_span_elems(m, n_src, st_s))
         h_dst = random_bits(rng, wl.pool_span_elems(m, n_dst, st_d))
-    src = Side(m, n_src, h_src, s_tabs, ks, st_s, host_ids)
-    dst = Side(m, n_dst, h_dst, d_tabs, ks, st_d, host_ids)
+    src = Side(m, n_src, h_src, s_tabs, ks, st_s, host_ids, start)
+    dst = Side(m, n_dst, h_dst, d_tabs, ks, st_d, host_ids, start)
     return src, dst
 
 
@@ -94,5 +96,5 @@ def oracle_migrate(orc, src, dst):
     m = src.m
     exp = dst.host.copy()
     orc.migrate(src.host, src.st, exp, dst.st, m.L, m.H, m.D, m.B, src.off, src.blk, dst.off,
-                dst.blk, src.k)
+                dst.blk, src.k, start=src.start)
     return exp

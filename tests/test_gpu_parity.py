@@ -34,12 +34,14 @@ def run_all_three(orc, src, dst):
 
     dst.dev.copy_(to_dev(dst.host))
     n_stage = kvm.kvm_staging_bytes(src.layout, src.batch)
-    assert n_stage == int(src.k.astype(np.int64).sum()) * m.bytes_per_token
+    moved = src.k.astype(np.int64) - (0 if src.start is None else src.start)
+    assert n_stage == int(moved.sum()) * m.bytes_per_token
     guard = 64
     stage = torch.full((n_stage + guard,), 0x5A, dtype=torch.uint8, device=DEV)
     kvm.kvm_pack(src.pool, src.batch, stage, staging_bytes=n_stage)
     torch.cuda.synchronize()
-    exp_stage = orc.pack(src.host, src.st, m.L, m.H, m.D, m.B, src.off, src.blk, src.k)
+    exp_stage = orc.pack(src.host, src.st, m.L, m.H, m.D, m.B, src.off, src.blk, src.k,
+                         start=src.start)
     s_host = stage.cpu().numpy()
     assert np.array_equal(s_host[:n_stage].view(np.uint16), exp_stage), "kvm_pack differs"
     assert (s_host[n_stage:] == 0x5A).all(), "kvm_pack wrote past the staging size"
@@ -175,3 +177,71 @@ def test_prefix_then_longer_prefix(oracle):
         kvm.kvm_migrate(src.pool, sb, dst.pool, db)
     torch.cuda.synchronize()
     assert np.array_equal(to_host(dst.dev), exp)
+
+
+def test_divider_classes_drive_the_migration(oracle):
+    """Hybrid migration end to end: the divider picks KV or token transfer per
+    request, KV-class requests move with k = len, token-class ones with k = 0."""
+    m = wl.Model("d", 2, 4, 4, 64, 16, "f16")
+    lens = [90, 40, 130, 64, 17, 200]
+    moves = [(0, 0, ln * m.bytes_per_token, ln) for ln in lens]
+    comm, comp = [260 * m.bytes_per_token], [150]
+    cls = kvm.kvm_divide_moves(moves, comm, comp, kvm.KVM_FIRST_FIT)
+    assert list(cls) == oracle.divide_moves(moves, comm, comp, "first_fit")
+    assert set(cls) == {kvm.KVM_CLASS_KV, kvm.KVM_CLASS_TOKENS, kvm.KVM_CLASS_DEFER}
+    keep = [i for i, c in enumerate(cls) if c != kvm.KVM_CLASS_DEFER]
+    ks = [lens[i] if cls[i] == kvm.KVM_CLASS_KV else 0 for i in keep]
+    src, dst = make_pair(m, 48, 48, [lens[i] for i in keep], ks, seed=31)
+    run_all_three(oracle, src, dst)
+
+
+@pytest.mark.parametrize("order", [0, 5])
+def test_token_ranges(oracle, order):
+    """Rounds of a live migration: only tokens [start, k) move, in all three paths."""
+    try:
+        kvm.kvm_set_option("copy.order", order)
+        m = wl.Model("r", 2, 3, 3, 128, 16, "bf16")
+        lens = [100, 64, 33, 48, 20, 7, 90]
+        ks = [100, 64, 33, 40, 20, 7, 81]
+        st = [37, 16, 32, 0, 20, 3, 80]     # mid-block, block-aligned, last block only, none, empty, ...
+        src, dst = make_pair(m, 48, 48, lens, ks, seed=41, start=st)
+        run_all_three(oracle, src, dst)
+        # strided destination
+        slot = m.H * m.D + 8
+        tm = np.array([2 * m.B * slot, m.B * slot, m.L * 2 * m.B * slot, m.D, slot], dtype=np.int64)
+        src, dst = make_pair(m, 48, 48, lens, ks, seed=42, dst_strides=tm, start=st)
+        run_all_three(oracle, src, dst)
+    finally:
+        kvm.kvm_set_option("copy.order", DEFAULTS[2])
+
+
+def test_live_migration_rounds_equal_one_shot(oracle):
+    """Copy [0,k0), let the request grow, copy [k0,k1), ... : the destination ends
+    as if [0,k_last) had been moved at once, and each round moves only its range."""
+    m = wl.Model("lv", 2, 4, 8, 128, 16, "f16")
+    src, dst = make_pair(m, 32, 32, [200], [200], seed=43)
+    exp = oracle_migrate(oracle, src, dst)
+    rounds = [0, 150, 183, 199, 200]
+    moved_bytes = 0
+    for a, b in zip(rounds, rounds[1:]):
+        sb = kvm.Batch(src.off, src.blk, [b], src.blk_dev, start=[a])
+        db = kvm.Batch(dst.off, dst.blk, [b], dst.blk_dev, start=[a])
+        moved_bytes += kvm.kvm_staging_bytes(src.layout, sb)
+        kvm.kvm_migrate(src.pool, sb, dst.pool, db)
+    torch.cuda.synchronize()
+    assert moved_bytes == 200 * m.bytes_per_token
+    assert np.array_equal(to_host(dst.dev), exp)
+
+
+def test_range_argument_errors():
+    m = wl.TINY
+    src, dst = make_pair(m, 8, 8, [40], [40], seed=44)
+    for start_s, start_d in (([41], [41]), ([-1], [-1]), ([8], [9]), ([8], None)):
+        sb = kvm.Batch(src.off, src.blk, [40], src.blk_dev, start=start_s)
+        db = kvm.Batch(dst.off, dst.blk, [40], dst.blk_dev, start=start_d)
+        with pytest.raises(kvm.KvmError) as e:
+            kvm.kvm_migrate(src.pool, sb, dst.pool, db)
+        assert e.value.status == kvm.KVM_EINVAL
+    sb = kvm.Batch(src.off, src.blk, [40], src.blk_dev, start=[8])
+    with pytest.raises(kvm.KvmError):
+        kvm.kvm_paged_decode(src.pool, sb, src.dev, src.dev)

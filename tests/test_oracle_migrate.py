@@ -307,6 +307,55 @@ def test_brute_force_all_k_and_all_permutations(oracle):
                 assert np.array_equal(last, view6(dst0, m, nblk)[:, :, pd[-1], :, m.B - 1])
 
 
+# --- token ranges (rounds of a live migration) ----------------------------------
+
+def test_ranges_compose_and_touch_only_their_slots(oracle):
+    m = wl.Model("rg", 2, 2, 2, 8, 4, "f16")
+    rng = np.random.default_rng(8)
+    nblk, ln = 12, 40
+    st = oracle.canonical_strides(m.L, m.H, m.D, m.B, nblk)
+    src, dst0 = random_pool(rng, m, nblk), random_pool(rng, m, nblk)
+    ts, td = rng.permutation(nblk)[:10].astype(np.int32), rng.permutation(nblk)[:10].astype(np.int32)
+    whole = {}
+    for b in range(0, ln + 1):
+        d = dst0.copy()
+        oracle.migrate(src, st, d, st, m.L, m.H, m.D, m.B, [0, 10], ts, [0, 10], td, [b])
+        whole[b] = d
+    for a in range(0, ln + 1, 3):
+        for b in range(a, ln + 1):
+            # [0,a) then [a,b) leaves the destination as [0,b) at once
+            d = whole[a].copy()
+            oracle.migrate(src, st, d, st, m.L, m.H, m.D, m.B, [0, 10], ts, [0, 10], td, [b], start=[a])
+            assert np.array_equal(d, whole[b]), (a, b)
+            # the range alone writes exactly the slots of tokens [a,b)
+            d = dst0.copy()
+            oracle.migrate(src, st, d, st, m.L, m.H, m.D, m.B, [0, 10], ts, [0, 10], td, [b], start=[a])
+            touched = np.zeros(d.size, bool)
+            t6 = view6(touched, m, nblk)
+            for t in range(a, b):
+                t6[:, :, td[t // m.B], :, t % m.B] = True
+            assert np.array_equal(d[~touched], dst0[~touched])
+            assert np.array_equal(d[touched], whole[b][touched])
+            # staging of the range is the slice [a,b) of the logical view, and unpack inverts it
+            stage = oracle.pack(src, st, m.L, m.H, m.D, m.B, [0, 10], ts, [b], start=[a])
+            assert stage.size * 2 == (b - a) * m.bytes_per_token
+            if b > a:
+                assert np.array_equal(stage.reshape(m.L, 2, m.H, b - a, m.D),
+                                      logical(src, m, nblk, ts, b)[:, :, :, a:])
+            e = dst0.copy()
+            oracle.unpack(stage, e, st, m.L, m.H, m.D, m.B, [0, 10], td, [b], start=[a])
+            assert np.array_equal(e, d)
+    # batches: per-request ranges, staging concatenated in batch order
+    ks, ss = [17, 9, 14], [5, 9, 0]
+    s_tabs, d_tabs = _small_batch(rng, m, nblk, [17, 9, 14], ks)
+    s_off, s_blk = csr(s_tabs)
+    d_off, d_blk = csr(d_tabs)
+    stage = oracle.pack(src, st, m.L, m.H, m.D, m.B, s_off, s_blk, ks, start=ss)
+    parts = [oracle.pack(src, st, m.L, m.H, m.D, m.B, [0, len(t)], t, [k], start=[s0])
+             for t, k, s0 in zip(s_tabs, ks, ss)]
+    assert np.array_equal(stage, np.concatenate(parts))
+
+
 # --- allocator -----------------------------------------------------------------
 
 def test_freelist_brute_force(oracle):

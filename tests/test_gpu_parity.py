@@ -245,3 +245,19 @@ def test_range_argument_errors():
     sb = kvm.Batch(src.off, src.blk, [40], src.blk_dev, start=[8])
     with pytest.raises(kvm.KvmError):
         kvm.kvm_paged_decode(src.pool, sb, src.dev, src.dev)
+
+
+def test_block_major_and_token_major_pools_at_model_shape(oracle):
+    """Other pool layouts are descriptor changes: a block-major pool (all planes of a
+    block adjacent) with token-major blocks on one side, the dense layout on the
+    other, at the 8B-GQA shape (shrunken pool)."""
+    m = wl.LLAMA3_8B
+    n = 24
+    L, H, D, B = m.L, m.H, m.D, m.B
+    block_token_major = np.array([2 * B * H * D, B * H * D, L * 2 * B * H * D, D, H * D], dtype=np.int64)
+    block_head_major = np.array([2 * H * B * D, H * B * D, L * 2 * H * B * D, B * D, D], dtype=np.int64)
+    lens, ks = [70, 33, 16], [61, 33, 9]
+    for ss, ds in ((block_token_major, None), (None, block_head_major),
+                   (block_head_major, block_token_major)):
+        src, dst = make_pair(m, n, n, lens, ks, seed=51, src_strides=ss, dst_strides=ds)
+        run_all_three(oracle, src, dst)

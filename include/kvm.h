@@ -180,7 +180,10 @@ int kvm_migrate(const kvm_pool* src, const kvm_batch* src_reqs, const kvm_pool* 
  * over several workgroups (size from kvm_decode_workspace_bytes; 16-byte
  * aligned).  NULL or too small a workspace is legal: the context is then not
  * split.  The result depends only on logical token positions, never on which
- * physical blocks hold them. */
+ * physical blocks hold them.  reqs->start must be NULL or all zero.
+ * block_tokens 16 with head_dim 64 or 128 runs the tuned kernel; any other block
+ * size and head_dim up to 512 runs a plain fallback kernel (head_dim > 512 is
+ * KVM_EINVAL). */
 int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev,
                      void* out_dev, int out_is_f32, float scale, void* workspace_dev,
                      int64_t workspace_bytes, void* hip_stream);

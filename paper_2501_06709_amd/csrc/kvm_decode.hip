@@ -362,6 +362,63 @@ __global__ __launch_bounds__(D) void merge_kernel(const DecArgs a) {
     reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
 }
 
+// Fallback for shapes the tiled kernel is not instantiated for (any block size,
+// head_dim a multiple of 8 up to 512): one wave per (request, layer, query head),
+// one token per iteration, lane c owning dims 8c..8c+7 of the row.  Correct and
+// in bounds for every layout the descriptor can express, not tuned.
+template <bool BF16>
+__global__ __launch_bounds__(64) void decode_generic_kernel(const DecArgs a, int D, int B) {
+  const int hq = blockIdx.x, l = blockIdx.y;
+  const DecReq rq = a.req[blockIdx.z];
+  const int k = rq.k;
+  if (k <= 0) return;
+  const int lane = threadIdx.x;
+  const bool active = lane < D / 8;
+  const int h = hq / (a.Hq / a.H);
+  uint32_t qv[4] = {0u, 0u, 0u, 0u};
+  if (active) {
+    const uint16_t* qptr = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + lane * 8;
+    const v4u raw = *reinterpret_cast<const v4u*>(qptr);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qv[c] = raw[c];
+  }
+  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + lane * 16;
+  const char* vbase = kbase + a.stride_kv;
+  float m = kNegBig, lsum = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < k; ++t) {
+    const int64_t blk = a.bt[rq.bt + t / B];
+    const int64_t off = blk * a.stride_block + (int64_t)(t % B) * a.stride_slot;
+    v4u kr = {0u, 0u, 0u, 0u}, vr = {0u, 0u, 0u, 0u};
+    if (active) {
+      kr = *reinterpret_cast<const v4u*>(kbase + off);
+      vr = *reinterpret_cast<const v4u*>(vbase + off);
+    }
+    float s = dot8<BF16>(qv, kr);
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d);
+    s *= a.scale_log2e;
+    const float mx = fmaxf(m, s);
+    const float alpha = __builtin_amdgcn_exp2f(m - mx), p = __builtin_amdgcn_exp2f(s - mx);
+    m = mx;
+    lsum = lsum * alpha + p;
+    float vf[8];
+    widen8<BF16>(vr, vf);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] = fmaf(p, vf[c], o[c] * alpha);
+  }
+  if (active) {
+    const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + lane * 8;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float res = o[c] / lsum;
+      if (a.out_f32)
+        reinterpret_cast<float*>(a.out)[oi + c] = res;
+      else
+        reinterpret_cast<uint16_t*>(a.out)[oi + c] = narrow<BF16>(res);
+    }
+  }
+}
+
 struct DecodePlan {
   int g_tile;    // query heads per workgroup (1, 2 or 4)
   int passes;    // workgroups per KV head
@@ -421,7 +478,8 @@ int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* re
   for (int r = 0; r < reqs->n_req; ++r)
     max_nb = std::max<int64_t>(max_nb, ceil_div(std::max(reqs->k[r], 0), layout->block_tokens));
   const DecodePlan p = plan_decode(*layout, reqs->n_req, max_nb);
-  return p.n_splits > 1 ? ws_bytes_for(*layout, reqs->n_req, p.n_splits) : 0;
+  const bool tiled = layout->block_tokens == 16 && (layout->head_dim == 64 || layout->head_dim == 128);
+  return tiled && p.n_splits > 1 ? ws_bytes_for(*layout, reqs->n_req, p.n_splits) : 0;
 }
 
 int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
@@ -440,11 +498,13 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
   if (!(scale >= 0.f) || !std::isfinite(scale))
     return fail(KVM_EINVAL, "kvm_paged_decode: scale must be finite and >= 0");
   const kvm_layout& l = pool->layout;
-  if (l.block_tokens != 16 || (l.head_dim != 64 && l.head_dim != 128))
-    return fail(KVM_EINVAL, "kvm_paged_decode: supported shapes are block_tokens 16, head_dim 64 or 128");
+  const bool tiled = l.block_tokens == 16 && (l.head_dim == 64 || l.head_dim == 128);
+  if (l.head_dim > 512)
+    return fail(KVM_EINVAL, "kvm_paged_decode: supported shapes have head_dim <= 512");
   int max_nb = 0;
   for (int r = 0; r < v.n_req; ++r) max_nb = std::max(max_nb, v.nb[r]);
   DecodePlan p = plan_decode(l, v.n_req, max_nb);
+  if (!tiled) p.n_splits = 1;  // the fallback kernel does not split contexts
   if (p.n_splits > 1) {
     // an absent or short workspace only limits how far the context is split
     const int64_t per_split = ws_bytes_for(l, v.n_req, 1);
@@ -484,10 +544,18 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
     hipError_t e;
     const hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = l.dtype == KVM_BF16;
-    if (l.head_dim == 128)
+    if (!tiled) {
+      const dim3 grid(a.Hq, a.L, n);
+      if (bf)
+        hipLaunchKernelGGL(decode_generic_kernel<true>, grid, dim3(64), 0, st, a, l.head_dim, l.block_tokens);
+      else
+        hipLaunchKernelGGL(decode_generic_kernel<false>, grid, dim3(64), 0, st, a, l.head_dim, l.block_tokens);
+      e = hipGetLastError();
+    } else if (l.head_dim == 128) {
       e = bf ? launch_decode<128, 16, true>(a, p, n, st) : launch_decode<128, 16, false>(a, p, n, st);
-    else
+    } else {
       e = bf ? launch_decode<64, 16, true>(a, p, n, st) : launch_decode<64, 16, false>(a, p, n, st);
+    }
     if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
   }
   return KVM_OK;

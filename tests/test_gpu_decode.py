@@ -150,3 +150,27 @@ def test_decode_after_migration_is_bitwise_the_same(oracle):
     kvm.kvm_migrate(src.pool, src.batch, alt.pool, alt.batch)
     c = gpu_decode(alt, q)
     assert np.array_equal(a, c)
+
+
+GENERIC = [
+    wl.Model("d80", 2, 2, 4, 80, 16, "f16"),      # head_dim not a power of two
+    wl.Model("d256", 1, 2, 2, 256, 16, "bf16"),
+    wl.Model("b8", 2, 3, 3, 64, 8, "bf16"),       # other block sizes
+    wl.Model("b32", 1, 2, 6, 128, 32, "f16"),
+    wl.Model("d512", 1, 1, 2, 512, 4, "f16"),
+]
+
+
+@pytest.mark.parametrize("m", GENERIC, ids=[s.name for s in GENERIC])
+def test_fallback_kernel_for_other_shapes(oracle, m):
+    lens = [1, m.B - 1, m.B, m.B + 1, 5 * m.B + 3, 150]
+    src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=27, finite=True)
+    side = Side(m, 64, src.host, src.tables, [lens[0], 0] + lens[2:])
+    q = wl.gen_q(27, m, len(lens))
+    got = gpu_decode(side, q)
+    ref = oracle_decode(oracle, side, q)
+    assert (got[1] == 7.0).all()
+    keep = [0, 2, 3, 4, 5]
+    assert np.abs(got[keep] - ref[keep]).max() < TOL
+    got16 = wl.bits16_to_f64(gpu_decode(side, q, out_f32=False).view(np.uint16), m.dtype)
+    assert np.abs(got16[keep] - ref[keep]).max() < 0.05

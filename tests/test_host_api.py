@@ -121,7 +121,7 @@ def test_argument_errors_come_before_any_launch():
     # decode
     assert "q_dev" in _einval(kvm.kvm_paged_decode, src, ok_s, None, FAKE)
     assert "scale" in _einval(kvm.kvm_paged_decode, src, ok_s, FAKE, FAKE, scale=-1.0)
-    odd = _pool(m=wl.Model("o", 2, 4, 4, 32, 16, "f16"))
+    odd = _pool(m=wl.Model("o", 2, 4, 4, 1024, 16, "f16"))
     assert "supported shapes" in _einval(kvm.kvm_paged_decode, odd, ok_s, FAKE, FAKE)
 
 

@@ -328,6 +328,153 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   return KVM_OK;
 }
 
+// ---- staging-linear pack / unpack -------------------------------------------
+// A second mapping for the staged path: the work is cut along the staging buffer
+// instead of along pool blocks.  One workgroup moves U*256 consecutive 16-byte
+// vectors of one (request, plane, head) run of the staging buffer, so consecutive
+// workgroups walk the staging buffer linearly and every workgroup touches one
+// contiguous staging range; the pool side is then a gather (pack) or scatter
+// (unpack) of token rows, each lane looking its block id up in the table.
+struct StageReq {
+  int32_t bt;         // first table entry of the request
+  int32_t start;      // first token moved
+  int32_t n_tok;      // tokens moved: k - start
+  int32_t chunks;     // workgroups per (plane, head) run
+  int64_t first_wg;   // first workgroup of the request in this launch
+  int64_t stage_vec;  // staging offset of the request in 16-byte vectors
+};
+
+struct StageArgs {
+  PoolSide pool;
+  char* stage;
+  int32_t n_req;
+  int32_t n_planes;
+  int32_t H, B;
+  uint32_t DV;
+  int32_t dv_shift, b_shift;  // log2 of DV and B, or -1
+  StageReq req[kMaxReqPerLaunch];
+};
+
+template <bool PACK, int U, bool NT>
+__global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
+  const int64_t wg = blockIdx.x;
+  int r = 0;
+#pragma unroll
+  for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
+    const int t = r + s;
+    if (t < a.n_req && a.req[t].first_wg <= wg) r = t;
+  }
+  const StageReq rq = a.req[r];
+  uint32_t local = (uint32_t)(wg - rq.first_wg);
+  const uint32_t chunk = local % (uint32_t)rq.chunks;
+  local /= (uint32_t)rq.chunks;
+  const uint32_t h = local % (uint32_t)a.H;
+  const uint32_t plane = local / (uint32_t)a.H;
+  const uint32_t n_vec = (uint32_t)rq.n_tok * a.DV;  // vectors of this (plane, head) run
+  const uint32_t x0 = chunk * (U * 256u) + threadIdx.x;
+  const uint32_t x_last = n_vec - 1;
+  char* pbase = a.pool.base + (uint64_t)(plane >> 1) * a.pool.stride_layer +
+                (uint64_t)(plane & 1) * a.pool.stride_kv + (uint64_t)h * a.pool.stride_head;
+  char* sbase = a.stage + ((uint64_t)rq.stage_vec + ((uint64_t)plane * a.H + h) * n_vec) * 16u;
+
+  int32_t blk[U];
+  uint32_t inner[U];  // byte offset of the lane's vector inside its block
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t x = min(x0 + u * 256u, x_last);  // lanes past the end repeat the last vector
+    const uint32_t tok = a.dv_shift >= 0 ? (x >> a.dv_shift) : (x / a.DV);
+    const uint32_t dv = x - tok * a.DV;
+    const uint32_t t = (uint32_t)rq.start + tok;
+    const uint32_t j = a.b_shift >= 0 ? (t >> a.b_shift) : (t / (uint32_t)a.B);
+    const uint32_t slot = t - j * (uint32_t)a.B;
+    blk[u] = a.pool.bt[rq.bt + (int32_t)j];
+    inner[u] = slot * a.pool.stride_slot + dv * 16u;
+  }
+  v4u val[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t x = min(x0 + u * 256u, x_last);
+    const char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
+    val[u] = load16(PACK ? pp : sbase + (uint64_t)x * 16u, NT);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t x = x0 + u * 256u;
+    if (x < n_vec) {
+      char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
+      store16(PACK ? sbase + (uint64_t)x * 16u : pp, val[u], NT);
+    }
+  }
+}
+
+template <bool PACK>
+static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& view, char* stage,
+                     hipStream_t stream) {
+  const kvm_layout& l = pool->layout;
+  const Options& o = options();
+  // one vector per lane measured best: the finer the workgroups, the more
+  // sequential the stream that reaches the staging buffer's DRAM pages
+  const int U = o.copy_unroll ? o.copy_unroll : 1;
+  StageArgs a;
+  memset(&a, 0, sizeof a);
+  a.pool = make_side(pool, b);
+  a.stage = stage;
+  a.n_planes = 2 * l.n_layers;
+  a.H = l.n_kv_heads;
+  a.B = l.block_tokens;
+  a.DV = (uint32_t)(l.head_dim * 2 / 16);
+  a.dv_shift = ilog2_exact(a.DV);
+  a.b_shift = ilog2_exact((uint32_t)a.B);
+  const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;
+  int64_t stage_vec = 0;
+  int r = 0;
+  while (r < view.n_req) {
+    a.n_req = 0;
+    int64_t n_wg = 0;
+    while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
+      const int64_t n_tok = view.k[r] - view.start[r];
+      const int64_t chunks = ceil_div(n_tok * a.DV, (int64_t)U * 256);
+      const int64_t wgs = chunks * a.n_planes * a.H;
+      if (wgs > 0x7fffffff) return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
+      if (n_wg + wgs > 0x7fffffff) break;
+      if (n_tok > 0) {  // requests that move nothing take no descriptor
+        StageReq& q = a.req[a.n_req++];
+        q.bt = view.bt_off[r];
+        q.start = view.start[r];
+        q.n_tok = (int32_t)n_tok;
+        q.chunks = (int32_t)chunks;
+        q.first_wg = n_wg;
+        q.stage_vec = stage_vec;
+        n_wg += wgs;
+      }
+      stage_vec += n_tok * bpt_vec;
+      ++r;
+    }
+    if (n_wg == 0) continue;
+    const dim3 grid((uint32_t)n_wg), block(256);
+#define KVM_STAGE(UU, NT) hipLaunchKernelGGL((stage_kernel<PACK, UU, NT>), grid, block, 0, stream, a)
+    if (o.copy_nontemporal) {
+      switch (U) {
+        case 1: KVM_STAGE(1, true); break;
+        case 2: KVM_STAGE(2, true); break;
+        case 8: KVM_STAGE(8, true); break;
+        default: KVM_STAGE(4, true); break;
+      }
+    } else {
+      switch (U) {
+        case 1: KVM_STAGE(1, false); break;
+        case 2: KVM_STAGE(2, false); break;
+        case 8: KVM_STAGE(8, false); break;
+        default: KVM_STAGE(4, false); break;
+      }
+    }
+#undef KVM_STAGE
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
+  }
+  return KVM_OK;
+}
+
 static bool same_shape(const kvm_layout& a, const kvm_layout& b) {
   return a.n_layers == b.n_layers && a.n_kv_heads == b.n_kv_heads && a.n_q_heads == b.n_q_heads &&
          a.head_dim == b.head_dim && a.block_tokens == b.block_tokens && a.dtype == b.dtype;
@@ -349,6 +496,8 @@ int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
   if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_pack: staging_dev is NULL");
   if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_pack: staging_dev is not 16-byte aligned");
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_pack: staging buffer too small");
+  if (options().stage_linear & 1)
+    return run_stage<true>(src, src_reqs, sv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kPack>(src, src_reqs, sv, src, src_reqs, sv, (char*)staging_dev,
                          (hipStream_t)hip_stream);
 }
@@ -363,6 +512,8 @@ int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* d
   if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is NULL");
   if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is not 16-byte aligned");
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_unpack: staging buffer too small");
+  if (options().stage_linear & 2)
+    return run_stage<false>(dst, dst_reqs, dv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kUnpack>(dst, dst_reqs, dv, dst, dst_reqs, dv, (char*)staging_dev,
                            (hipStream_t)hip_stream);
 }

@@ -43,6 +43,7 @@ struct Options {
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
   int copy_order = 0;         // 0..3: how consecutive workgroups walk (chunk, plane, block)
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
+  int stage_linear = 3;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits
 };

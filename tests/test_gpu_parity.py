@@ -261,3 +261,37 @@ def test_block_major_and_token_major_pools_at_model_shape(oracle):
                    (block_head_major, block_token_major)):
         src, dst = make_pair(m, n, n, lens, ks, seed=51, src_strides=ss, dst_strides=ds)
         run_all_three(oracle, src, dst)
+
+
+@pytest.mark.parametrize("mode,unroll", [(0, 0), (1, 0), (2, 0), (3, 4), (3, 8), (0, 2)])
+def test_staging_linear_mapping(oracle, mode, unroll):
+    """pack / unpack cut along the staging buffer instead of along pool blocks."""
+    try:
+        kvm.kvm_set_option("copy.stage_linear", mode)
+        kvm.kvm_set_option("copy.unroll", unroll)
+        m = wl.Model("sl", 2, 3, 3, 128, 16, "bf16")
+        lens = [100, 64, 33, 48, 20, 7, 90, 1]
+        ks = [100, 64, 33, 40, 20, 7, 81, 1]
+        src, dst = make_pair(m, 48, 48, lens, ks, seed=61)
+        run_all_three(oracle, src, dst)
+        st = [37, 16, 32, 0, 20, 3, 80, 0]
+        src, dst = make_pair(m, 48, 48, lens, ks, seed=62, start=st)
+        run_all_three(oracle, src, dst)
+        # token-major padded pool, odd head_dim / block size (no power-of-two shortcuts)
+        m2 = wl.Model("sl2", 2, 2, 2, 80, 12, "f16")
+        slot = m2.H * m2.D + 8
+        tm = np.array([2 * m2.B * slot, m2.B * slot, m2.L * 2 * m2.B * slot, m2.D, slot], dtype=np.int64)
+        src, dst = make_pair(m2, 30, 30, [50, 12, 25], [41, 12, 13], seed=63, src_strides=tm,
+                             start=[5, 0, 12])
+        run_all_three(oracle, src, dst)
+        # more requests than one launch carries, some moving nothing
+        m3 = wl.Model("sl3", 1, 2, 2, 64, 16, "f16")
+        rng = np.random.default_rng(64)
+        lens3 = [int(x) for x in rng.integers(1, 40, size=150)]
+        ks3 = [int(rng.integers(0, ln + 1)) for ln in lens3]
+        n = sum(-(-ln // 16) for ln in lens3) + 7
+        src, dst = make_pair(m3, n, n, lens3, ks3, seed=65)
+        run_all_three(oracle, src, dst)
+    finally:
+        kvm.kvm_set_option("copy.stage_linear", 3)
+        kvm.kvm_set_option("copy.unroll", DEFAULTS[0])

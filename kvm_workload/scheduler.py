@@ -350,6 +350,8 @@ class Scheduler:
 @dataclass
 class Trace:
     orders: list            # per slot: list of (request id, src gpu id, dst gpu id, bytes)
+    departures: list        # per slot: request ids that completed (applied first)
+    arrivals: list          # per slot: (request id, gpu id at the end of the slot, bytes)
     gpus_per_slot: list
     lower_bound_per_slot: list
     max_moves_per_op: int
@@ -373,6 +375,7 @@ def simulate(capacity, bytes_per_token, n_slots=200, arrival_rate=0.8, median=76
     live = {}       # rid -> [tokens, final tokens]
     rid_next = 0
     orders, gpus_per_slot, lb, worst = [], [], [], 0
+    departures, arrivals = [], []
     req_unbatched = 0
 
     def gpu_of(rid):
@@ -415,6 +418,7 @@ def simulate(capacity, bytes_per_token, n_slots=200, arrival_rate=0.8, median=76
         moves_before = sch.total_request_moves
         # (1) departures
         done = [rid for rid, (tok, fin) in live.items() if tok >= fin]
+        departures.append(list(done))
         for rid in done:
             del live[rid]
             start_place.pop(rid)
@@ -463,6 +467,8 @@ def simulate(capacity, bytes_per_token, n_slots=200, arrival_rate=0.8, median=76
             if g1 != g0:
                 slot_orders.append((rid, g0, g1, sch.where[rid].members[rid]))
         orders.append(slot_orders)
+        arrivals.append([(rid, gpu_of(rid), sch.where[rid].members[rid]) for rid in live
+                         if rid not in start_place])
         req_unbatched += sch.total_request_moves - moves_before
         gpus_per_slot.append(len(sch.gpus))
         total = sum(it.size for g in sch.gpus for it in g.items)
@@ -470,5 +476,5 @@ def simulate(capacity, bytes_per_token, n_slots=200, arrival_rate=0.8, median=76
         if check:
             sch.check_capacity()
             worst = max(worst, sch.theorem1_violations())
-    return Trace(orders, gpus_per_slot, lb, sch.max_moves_per_op, sch.total_item_moves,
+    return Trace(orders, departures, arrivals, gpus_per_slot, lb, sch.max_moves_per_op, sch.total_item_moves,
                  sum(len(o) for o in orders), req_unbatched, worst, sch.peak_gpus)

@@ -2,13 +2,13 @@
 """Benchmark of the paged-KV migration hot path on one MI355X.
 
 A step is one pass of the whole path over the batch of requests to migrate:
-  a1  destination blocks popped from the destination free list, new block table
-      uploaded;
-  a2  kvm_pack   (gather into the staging buffer)
-  a4  kvm_unpack (scatter the staging buffer into the destination blocks)
-  a5  kvm_migrate (the same move fused, no staging; same destination tables)
-  a7  kvm_paged_decode over the destination cache
-  a6  source blocks returned to the source free list once the copies are done
+  1. destination blocks popped from the destination free list, new block table
+     uploaded;
+  2. kvm_pack   (gather into the staging buffer)
+  3. kvm_unpack (scatter the staging buffer into the destination blocks)
+  4. kvm_migrate (the same move fused, no staging; same destination tables)
+  5. kvm_paged_decode over the destination cache
+  6. source blocks returned to the source free list once the copies are done
 followed by the bookkeeping that lets the next step start from the same state
 (source ids reserved again, destination ids freed).  All of it is inside the
 timed region.
@@ -320,7 +320,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step(events):
-        # a1: allocate destination blocks, rewrite and upload the block table
+        # allocate destination blocks, rewrite and upload the block table
         ids = dst_fl.alloc(n_dst)
         d_blk_pin.numpy()[:n_dst] = ids
         d_blk_dev.copy_(d_blk_pin, non_blocking=True)
@@ -339,16 +339,16 @@ def main():
         for (lo, hi), sg in zip(groups, src_groups):
             dg = dst_batch if len(groups) == 1 else sub_batch(d_off, ids, d_blk_dev, lo, hi)
             nbytes = int(w.k[lo:hi].astype(np.int64).sum()) * m.bytes_per_token
-            timed("pack", lambda: kvm.kvm_pack(src_pool, sg, staging, staging_bytes=nbytes))    # a2
-            timed("unpack", lambda: kvm.kvm_unpack(staging, dst_pool, dg, staging_bytes=nbytes))  # a4
-        timed("migrate", lambda: kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch))      # a5
+            timed("pack", lambda: kvm.kvm_pack(src_pool, sg, staging, staging_bytes=nbytes))
+            timed("unpack", lambda: kvm.kvm_unpack(staging, dst_pool, dg, staging_bytes=nbytes))
+        timed("migrate", lambda: kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch))
         done = torch.cuda.Event()
         done.record(stream)
         timed("decode", lambda: kvm.kvm_paged_decode(dst_pool, dst_batch, q_dev, out, workspace=ws,
-                                                     workspace_bytes=ws_bytes))                  # a7
+                                                     workspace_bytes=ws_bytes))
         if events is not None:
             events.append(marks)
-        # a6: the source blocks may be released only once the copies have finished
+        # the source blocks may be released only once the copies have finished
         done.synchronize()
         src_fl.free(s_blk)
         # bookkeeping so that the next step starts from the same state

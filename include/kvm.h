@@ -248,8 +248,8 @@ const char* kvm_strerror(int status);
 const char* kvm_last_error(void);
 /* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
  * value gives KVM_EINVAL.  Names: "copy.unroll" (1,2,4,8 16-byte vectors per
- * lane per workgroup pass, 0 = automatic), "copy.nontemporal" (0/1), "copy.order" (0..5: how
- * consecutive workgroups walk chunk / plane / block entry), "copy.lds_pad_kb"
+ * lane per workgroup pass, 0 = automatic), "copy.nontemporal" (0/1), "copy.order" (0: consecutive
+ * workgroups walk the planes of one block; 1: plane outermost), "copy.lds_pad_kb"
  * (0..64: dynamic LDS per workgroup, caps residency), "decode.max_splits"
  * (1..64), "decode.force_splits" (0 = automatic, else exactly this many splits).
  * Process-wide; not thread-safe against concurrent launches. */

@@ -62,7 +62,7 @@ struct CopyArgs {
   int32_t H, B;
   uint32_t DV;         // 16-byte vectors per token row (head_dim*2/16)
   int32_t dv_shift;    // log2(DV) or -1
-  int32_t order;       // how consecutive workgroups walk (chunk, plane, block entry)
+  int32_t order;       // 0: planes of a block are consecutive workgroups; 1: plane outermost
   CopyReq req[kMaxReqPerLaunch];
 };
 
@@ -80,61 +80,21 @@ __device__ __forceinline__ void store16(char* p, v4u v, bool nt) {
 
 template <int MODE, int U, bool NT>
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
-  // ---- decode the work item (all wave-uniform) ----
-  uint32_t wg = blockIdx.x;
-  uint32_t chunk = 0, item = 0, plane = 0;
-  switch (a.order) {
-    case 1:  // chunk fastest, then block entry, plane outermost
-      chunk = wg % (uint32_t)a.n_chunks; wg /= (uint32_t)a.n_chunks;
-      item = wg % (uint32_t)a.n_items; plane = wg / (uint32_t)a.n_items;
-      break;
-    case 2:  // plane fastest, then chunk, block entry outermost
-      plane = wg % (uint32_t)a.n_planes; wg /= (uint32_t)a.n_planes;
-      chunk = wg % (uint32_t)a.n_chunks; item = wg / (uint32_t)a.n_chunks;
-      break;
-    case 3:  // plane fastest, then block entry, chunk outermost
-      plane = wg % (uint32_t)a.n_planes; wg /= (uint32_t)a.n_planes;
-      item = wg % (uint32_t)a.n_items; chunk = wg / (uint32_t)a.n_items;
-      break;
-    case 5:
-      break;  // decoded below, once the request is known
-    case 4:  // block entry fastest, then chunk, plane outermost
-      item = wg % (uint32_t)a.n_items; wg /= (uint32_t)a.n_items;
-      chunk = wg % (uint32_t)a.n_chunks; plane = wg / (uint32_t)a.n_chunks;
-      break;
-    default:  // chunk fastest, then plane, block entry outermost
-      chunk = wg % (uint32_t)a.n_chunks; wg /= (uint32_t)a.n_chunks;
-      plane = wg % (uint32_t)a.n_planes; item = wg / (uint32_t)a.n_planes;
-      break;
-  }
+  // ---- decode the work item (all wave-uniform, no division) ----
+  // grid = (chunks, planes, block entries): consecutive workgroups walk the chunks
+  // of one (block, plane), then the planes of the block, then the next block.
+  // With order = 1 the last two are swapped (plane outermost), kept for comparison.
+  const uint32_t chunk = blockIdx.x;
+  const uint32_t plane = a.order ? blockIdx.z : blockIdx.y;
+  const uint32_t item = a.order ? blockIdx.y : blockIdx.z;
   // request that owns the item: largest r with first_item[r] <= item
   int r = 0;
-  int32_t j;
-  if (a.order == 5) {
-    // staging order: request outermost, then plane, chunk, and the request's
-    // blocks fastest, so consecutive workgroups walk the staging buffer linearly
-    const uint32_t per_item = (uint32_t)a.n_planes * (uint32_t)a.n_chunks;
-    wg = blockIdx.x;
 #pragma unroll
-    for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
-      const int t = r + s;
-      if (t < a.n_req && (uint32_t)a.req[t].first_item * per_item <= wg) r = t;
-    }
-    const uint32_t nb_r = (uint32_t)((r + 1 < a.n_req ? a.req[r + 1].first_item : a.n_items) -
-                                     a.req[r].first_item);
-    wg -= (uint32_t)a.req[r].first_item * per_item;
-    j = (int32_t)(wg % nb_r);
-    wg /= nb_r;
-    chunk = wg % (uint32_t)a.n_chunks;
-    plane = wg / (uint32_t)a.n_chunks;
-  } else {
-#pragma unroll
-    for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
-      const int t = r + s;
-      if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
-    }
-    j = (int32_t)item - a.req[r].first_item;  // block of the request, counted from its first moved one
+  for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
+    const int t = r + s;
+    if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
   }
+  int32_t j = (int32_t)item - a.req[r].first_item;  // block of the request, counted from its first moved one
   const CopyReq rq = a.req[r];
   j += rq.start / a.B;                          // logical block of the request
   // slots [s0, s1) of this block hold tokens of [start, k)
@@ -248,10 +208,11 @@ static int pick_unroll() {
 }
 
 template <int MODE>
-static hipError_t launch(const CopyArgs& a, uint32_t grid, hipStream_t stream) {
+static hipError_t launch(const CopyArgs& a, hipStream_t stream) {
   const Options& o = options();
+  const dim3 grid = a.order ? dim3(a.n_chunks, a.n_items, a.n_planes) : dim3(a.n_chunks, a.n_planes, a.n_items);
 #define KVM_LAUNCH(U, NT) \
-  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), dim3(grid), dim3(256), (size_t)o.copy_lds_pad_kb * 1024, stream, a)
+  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), grid, dim3(256), (size_t)o.copy_lds_pad_kb * 1024, stream, a)
   if (o.copy_nontemporal) {
     switch (pick_unroll<MODE>()) {
       case 1: KVM_LAUNCH(1, true); break;
@@ -303,11 +264,11 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   while (r < view.n_req) {
     a.n_req = 0;
     a.n_items = 0;
-    const int64_t max_items = (int64_t)0x7fffffff / ((int64_t)a.n_planes * a.n_chunks);
+    const int64_t max_items = 65535;  // grid dimension limit for y and z
     while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
       const int32_t items_r = view.nb[r] - view.jb[r];
       if (items_r > max_items)
-        return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
+        return fail(KVM_EINVAL, "a single request moves more than 65535 blocks in one call");
       if ((int64_t)a.n_items + items_r > max_items) break;
       CopyReq& q = a.req[a.n_req++];
       q.src_bt = sv.bt_off[r];
@@ -321,8 +282,7 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
       ++r;
     }
     if (a.n_items == 0) continue;  // only k = 0 requests in this group
-    const uint32_t grid = (uint32_t)((int64_t)a.n_items * a.n_planes * a.n_chunks);
-    const hipError_t e = launch<MODE>(a, grid, stream);
+    const hipError_t e = launch<MODE>(a, stream);
     if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
   }
   return KVM_OK;
@@ -335,11 +295,33 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
 // workgroups walk the staging buffer linearly and every workgroup touches one
 // contiguous staging range; the pool side is then a gather (pack) or scatter
 // (unpack) of token rows, each lane looking its block id up in the table.
+// Division of a 32-bit value by a fixed divisor d through one high multiply
+// (Granlund & Montgomery, "Division by invariant integers using multiplication"):
+// with l = ceil(log2 d) and m = floor(2^32 (2^l - d) / d) + 1,
+// floor(x / d) = (t + ((x - t) >> 1)) >> (l - 1), t = mulhi(x, m), for d > 1.
+struct FastDiv {
+  uint32_t d, m, sh;  // sh = l - 1; d = 1 is flagged by m = 0
+};
+static FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f{d, 0, 0};
+  if (d <= 1) return f;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.m = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+  f.sh = l - 1;
+  return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t x, const FastDiv& f) {
+  if (f.m == 0) return x;
+  const uint32_t t = __umulhi(x, f.m);
+  return (t + ((x - t) >> 1)) >> f.sh;
+}
+
 struct StageReq {
   int32_t bt;         // first table entry of the request
   int32_t start;      // first token moved
   int32_t n_tok;      // tokens moved: k - start
-  int32_t chunks;     // workgroups per (plane, head) run
+  FastDiv chunks;     // workgroups per (plane, head) run
   int64_t first_wg;   // first workgroup of the request in this launch
   int64_t stage_vec;  // staging offset of the request in 16-byte vectors
 };
@@ -352,6 +334,7 @@ struct StageArgs {
   int32_t H, B;
   uint32_t DV;
   int32_t dv_shift, b_shift;  // log2 of DV and B, or -1
+  FastDiv heads;              // division by H
   StageReq req[kMaxReqPerLaunch];
 };
 
@@ -365,11 +348,11 @@ __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
     if (t < a.n_req && a.req[t].first_wg <= wg) r = t;
   }
   const StageReq rq = a.req[r];
-  uint32_t local = (uint32_t)(wg - rq.first_wg);
-  const uint32_t chunk = local % (uint32_t)rq.chunks;
-  local /= (uint32_t)rq.chunks;
-  const uint32_t h = local % (uint32_t)a.H;
-  const uint32_t plane = local / (uint32_t)a.H;
+  const uint32_t local = (uint32_t)(wg - rq.first_wg);
+  const uint32_t run = fastdiv(local, rq.chunks);       // (plane, head) run of the request
+  const uint32_t chunk = local - run * rq.chunks.d;
+  const uint32_t plane = fastdiv(run, a.heads);
+  const uint32_t h = run - plane * a.heads.d;
   const uint32_t n_vec = (uint32_t)rq.n_tok * a.DV;  // vectors of this (plane, head) run
   const uint32_t x0 = chunk * (U * 256u) + threadIdx.x;
   const uint32_t x_last = n_vec - 1;
@@ -425,6 +408,7 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
   a.DV = (uint32_t)(l.head_dim * 2 / 16);
   a.dv_shift = ilog2_exact(a.DV);
   a.b_shift = ilog2_exact((uint32_t)a.B);
+  a.heads = make_fastdiv((uint32_t)a.H);
   const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;
   int64_t stage_vec = 0;
   int r = 0;
@@ -442,7 +426,7 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
         q.bt = view.bt_off[r];
         q.start = view.start[r];
         q.n_tok = (int32_t)n_tok;
-        q.chunks = (int32_t)chunks;
+        q.chunks = make_fastdiv((uint32_t)chunks);
         q.first_wg = n_wg;
         q.stage_vec = stage_vec;
         n_wg += wgs;

@@ -41,7 +41,7 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
 struct Options {
   int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
-  int copy_order = 0;         // 0..3: how consecutive workgroups walk (chunk, plane, block)
+  int copy_order = 0;         // 0: planes of a block consecutive (shipped); 1: plane outermost
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int stage_linear = 3;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
   int decode_max_splits = 16;

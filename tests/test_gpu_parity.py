@@ -96,7 +96,7 @@ def test_model_shapes_shrunken_pools(oracle, name, m, n_src, n_dst, lens, ks):
     run_all_three(oracle, src, dst)
 
 
-@pytest.mark.parametrize("unroll,nt,order", [(1, 0, 1), (2, 1, 0), (4, 0, 2), (8, 1, 3), (2, 0, 4), (1, 1, 5), (8, 0, 5)])
+@pytest.mark.parametrize("unroll,nt,order", [(1, 0, 1), (2, 1, 0), (4, 0, 0), (8, 1, 1), (2, 0, 1), (1, 1, 0), (8, 0, 0)])
 def test_every_launch_option(oracle, unroll, nt, order):
     try:
         kvm.kvm_set_option("copy.unroll", unroll)
@@ -195,7 +195,7 @@ def test_divider_classes_drive_the_migration(oracle):
     run_all_three(oracle, src, dst)
 
 
-@pytest.mark.parametrize("order", [0, 5])
+@pytest.mark.parametrize("order", [0, 1])
 def test_token_ranges(oracle, order):
     """Rounds of a live migration: only tokens [start, k) move, in all three paths."""
     try:

@@ -230,10 +230,19 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   // requested as soon as the scores of the current one are formed, V of the next
   // block as soon as the current V rows are accumulated, so a load is always in
   // flight while the other tile is being consumed.
+  // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, the other counters left at
+  // their maximum).  The explicit waits below keep the compiler from draining all
+  // loads at the top of every iteration: without them it cannot prove that the
+  // query registers (loaded before the loop) and the block-id register (reloaded
+  // inside a rare branch) are ready, and inserts vmcnt(0) on the hot path.
+  constexpr int kWaitAll = 0x0F70;
+  constexpr int kWaitAllButTiles = 0x0F70 | (2 * NI);   // 2*NI <= 8 tile loads may stay in flight
   if (n_it > 0) {
     fetch_ids(0);
+    __builtin_amdgcn_s_waitcnt(kWaitAll);
     load_k(0, kc);
     load_v(0, vc);
+    __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
   }
   for (int it = 0; it < n_it; ++it) {
     const bool more = it + 1 < n_it;
@@ -247,7 +256,10 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
       for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i])) * sc;
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
-      if (((it + 1) & 63) == 0) fetch_ids(it + 1);
+      if (((it + 1) & 63) == 0) {
+        fetch_ids(it + 1);
+        __builtin_amdgcn_s_waitcnt(kWaitAll);           // once per 64 blocks of this wave
+      }
       load_k(it + 1, kc);
     }
     __builtin_amdgcn_sched_barrier(0);

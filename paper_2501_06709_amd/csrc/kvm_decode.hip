@@ -347,6 +347,216 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   }
 }
 
+// Grouped-query variant with the K/V tile of a block staged in LDS and shared by
+// the four waves of the workgroup.  All waves walk all blocks of the range; every
+// lane fetches one 16-byte vector of the K tile and one of the V tile (two blocks
+// ahead, held in registers, then written to a two-stage LDS ring), and each wave
+// serves one query head (group 4) or half of the token rows of one head (group 2)
+// from the shared tile.  Against the register-tile kernel a wave holds 16 instead
+// of 32 tile registers and one head's accumulator instead of four, so more
+// workgroups stay resident and more bytes are in flight per CU.
+// LDS tile layout = the block-head run itself (token-major, 16 bytes per lane), so
+// lane x of read i reads bytes [i*1024 + x*16, +16): consecutive lanes, no bank
+// conflicts.
+template <int D, int B, int G, bool BF16>
+__global__ __launch_bounds__(256) void decode_shared_kernel(const DecArgs a) {
+  constexpr int LPT = D / 8;
+  constexpr int TPI = 64 / LPT;
+  constexpr int NI = B / TPI;
+  constexpr int WPH = 4 / G;       // waves per query head
+  constexpr int NIW = NI / WPH;    // 1 KiB row groups of a tile per wave
+  constexpr int NP = 4 * TPI;      // online-softmax states per workgroup
+  constexpr int TV = B * LPT;      // 16-byte vectors per K (or V) tile
+  static_assert(G == 2 || G == 4, "group of 2 or 4 query heads per KV head");
+  static_assert(NI % WPH == 0 && NIW >= 1, "tile rows must divide among the waves of a head");
+  static_assert(TV <= 256, "one vector per lane per tile");
+
+  __shared__ __attribute__((aligned(16))) char s_tile[2][2][TV * 16];  // [stage][K, V]
+  __shared__ float s_m[NP];
+  __shared__ float s_l[NP];
+  __shared__ __attribute__((aligned(16))) float s_o[NP][D];
+
+  const int pass = blockIdx.x % a.passes;
+  const int h = blockIdx.x / a.passes;
+  const int l = blockIdx.y;
+  const int r = blockIdx.z / a.n_splits;
+  const int split = blockIdx.z % a.n_splits;
+  const DecReq rq = a.req[r];
+  const int k = rq.k;
+  if (k <= 0) return;
+  const int nb = (k + B - 1) / B;
+  const int per = (nb + a.n_splits - 1) / a.n_splits;
+  const int jb = split * per;
+  const int je = min(nb, jb + per);
+  if (jb >= je) return;
+  const int n_it = je - jb;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int sub = lane % LPT;
+  const int row = lane / LPT;
+  const int g = wave % G;          // query head of this wave
+  const int part = wave / G;       // which row groups of the tile it takes
+  const int hq0 = (h * a.passes + pass) * G;
+
+  uint32_t qp[4];
+  {
+    const uint16_t* qptr = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0 + g) * D + sub * 8;
+    const v4u raw = *reinterpret_cast<const v4u*>(qptr);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qp[c] = raw[c];
+  }
+  const float sc = a.scale_log2e;
+  float m = kNegBig, lsum = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // loader role: lane `tid` moves vector `tid` of both tiles
+  const bool loader = tid < TV;
+  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head +
+                      (uint64_t)(tid / LPT) * a.stride_slot + (uint32_t)(tid % LPT) * 16u;
+  const char* vbase = kbase + a.stride_kv;
+  const char* dummy = reinterpret_cast<const char*>(
+      a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // always valid, 16-byte aligned
+  int ids = 0;
+  auto fetch_ids = [&](int it0) {
+    const int j = jb + it0 + lane;
+    ids = j < je ? a.bt[rq.bt + j] : 0;
+  };
+  constexpr int kWaitAll = 0x0F70;
+  auto gload = [&](int it, v4u& rk, v4u& rv) {
+    if ((it & 63) == 0 && it > 0 && it < n_it) {
+      fetch_ids(it);
+      __builtin_amdgcn_s_waitcnt(kWaitAll);   // once per 64 blocks
+    }
+    // Every call issues exactly two loads (lanes without a vector to fetch, and
+    // steps past the end of the range, read the query row instead): with a fixed
+    // number of loads per step the waits before the LDS writes can leave the
+    // younger loads in flight instead of draining them.
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
+    const bool real = loader && it < n_it;
+    const char* kp = real ? kbase + blk * a.stride_block : dummy;
+    const char* vp = real ? vbase + blk * a.stride_block : dummy;
+    rk = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp));
+    rv = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp));
+  };
+  auto lstore = [&](int stage, const v4u& rk, const v4u& rv) {
+    if (loader) {
+      *reinterpret_cast<v4u*>(&s_tile[stage][0][tid * 16]) = rk;
+      *reinterpret_cast<v4u*>(&s_tile[stage][1][tid * 16]) = rv;
+    }
+  };
+  auto compute = [&](int stage, int it) {
+    const int t_limit = k - (jb + it) * B;
+    const char* kt = &s_tile[stage][0][lane * 16];
+    const char* vt = &s_tile[stage][1][lane * 16];
+    float s[NIW];
+#pragma unroll
+    for (int ii = 0; ii < NIW; ++ii) {
+      const int i = part + ii * WPH;
+      const v4u kv = *reinterpret_cast<const v4u*>(kt + i * 1024);
+      s[ii] = group_sum<LPT>(dot8<BF16>(qp, kv)) * sc;
+    }
+    float mx = m;
+#pragma unroll
+    for (int ii = 0; ii < NIW; ++ii)
+      if ((part + ii * WPH) * TPI + row < t_limit) mx = fmaxf(mx, s[ii]);
+    const float alpha = __builtin_amdgcn_exp2f(m - mx);
+    m = mx;
+    float add = 0.f;
+#pragma unroll
+    for (int ii = 0; ii < NIW; ++ii) {
+      s[ii] = ((part + ii * WPH) * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[ii] - mx) : 0.f;
+      add += s[ii];
+    }
+    lsum = lsum * alpha + add;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] *= alpha;
+#pragma unroll
+    for (int ii = 0; ii < NIW; ++ii) {
+      const int i = part + ii * WPH;
+      v4u vv = *reinterpret_cast<const v4u*>(vt + i * 1024);
+      if (i * TPI + row >= t_limit) vv = v4u{0u, 0u, 0u, 0u};  // garbage past the context
+      float vf[8];
+      widen8<BF16>(vv, vf);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[c] = fmaf(s[ii], vf[c], o[c]);
+    }
+  };
+
+  // P register sets hold the blocks in flight, two LDS stages the blocks being
+  // consumed.  Entering step x: stage x&1 holds block x, set (x+1)%P block x+1
+  // (stored to the other stage during the step), sets for x+2 .. x+P-1 are in
+  // flight and set x%P is free for block x+P.
+  constexpr int P = 4;
+  v4u rk[P], rv[P];
+#pragma unroll
+  for (int u = 0; u < P; ++u) rk[u] = rv[u] = v4u{0u, 0u, 0u, 0u};
+  fetch_ids(0);
+  __builtin_amdgcn_s_waitcnt(kWaitAll);
+#pragma unroll
+  for (int u = 0; u < P; ++u) gload(u, rk[u], rv[u]);
+  lstore(0, rk[0], rv[0]);
+  __syncthreads();
+  for (int it = 0; it < n_it; it += P) {
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+      const int x = it + u;
+      if (x >= n_it) break;
+      gload(x + P, rk[u], rv[u]);
+      compute(u & 1, x);
+      if (x + 1 < n_it) lstore((u + 1) & 1, rk[(u + 1) % P], rv[(u + 1) % P]);
+      __syncthreads();   // next stage visible; every wave is done reading this one
+    }
+  }
+
+  // ---- merge the states of the waves that served the same head ----
+  const int slot = wave * TPI + row;
+  if (sub == 0) {
+    s_m[slot] = m;
+    s_l[slot] = lsum;
+  }
+  {
+    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][sub * 8]);
+    dst[0] = v4f{o[0], o[1], o[2], o[3]};
+    dst[1] = v4f{o[4], o[5], o[6], o[7]};
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * D; idx += 256) {
+    const int gg = idx / D, d = idx % D;
+    float mx = kNegBig;
+#pragma unroll
+    for (int p = 0; p < WPH; ++p)
+#pragma unroll
+      for (int rr = 0; rr < TPI; ++rr) mx = fmaxf(mx, s_m[(gg + G * p) * TPI + rr]);
+    float acc = 0.f, den = 0.f;
+#pragma unroll
+    for (int p = 0; p < WPH; ++p)
+#pragma unroll
+      for (int rr = 0; rr < TPI; ++rr) {
+        const int pidx = (gg + G * p) * TPI + rr;
+        const float wgt = __builtin_amdgcn_exp2f(s_m[pidx] - mx);
+        acc = fmaf(s_o[pidx][d], wgt, acc);
+        den = fmaf(s_l[pidx], wgt, den);
+      }
+    const int hq = hq0 + gg;
+    if (a.n_splits == 1) {
+      const float res = acc / den;
+      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
+      if (a.out_f32)
+        reinterpret_cast<float*>(a.out)[oi] = res;
+      else
+        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
+    } else {
+      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
+      e[d] = acc;
+      if (d == 0) {
+        e[D] = mx;
+        e[D + 1] = den;
+      }
+    }
+  }
+}
+
 // Log-sum-exp merge of the context splits, in split order.
 template <int D, int B, bool BF16>
 __global__ __launch_bounds__(D) void merge_kernel(const DecArgs a) {
@@ -466,9 +676,16 @@ static int64_t ws_bytes_for(const kvm_layout& l, int n_req, int n_splits) {
 template <int D, int B, bool BF16>
 static hipError_t launch_decode(const DecArgs& a, const DecodePlan& p, int n_req, hipStream_t st) {
   const dim3 grid(a.H * p.passes, a.L, n_req * p.n_splits);
+  const bool shared = options().decode_shared_tiles != 0;
   switch (p.g_tile) {
-    case 4: hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a); break;
+    case 4:
+      if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a);
+      break;
+    case 2:
+      if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a);
+      break;
     default: hipLaunchKernelGGL((decode_kernel<D, B, 1, BF16>), grid, dim3(256), 0, st, a); break;
   }
   hipError_t e = hipGetLastError();

@@ -44,6 +44,7 @@ struct Options {
   int copy_order = 0;         // 0: planes of a block consecutive (shipped); 1: plane outermost
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int stage_linear = 3;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
+  int decode_shared_tiles = 0;  // 1: grouped-query decode stages the K/V tile in LDS, one wave per query head
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits
 };

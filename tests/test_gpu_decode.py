@@ -50,13 +50,20 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("shared_tiles", [1, 0], ids=["lds_tiles", "register_tiles"])
 @pytest.mark.parametrize("m", SHAPES, ids=[s.name for s in SHAPES])
-def test_decode_matches_oracle(oracle, m):
+def test_decode_matches_oracle(oracle, m, shared_tiles):
+    """Both grouped-query kernels (K/V tile shared through LDS, or per-wave register
+    tiles) and the MHA kernel against the fp64 oracle."""
     lens = [1, 15, 16, 17, 100, 333, 64]
     src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=21, finite=True)
     side = Side(m, 64, src.host, src.tables, lens)
     q = wl.gen_q(21, m, len(lens))
-    got = gpu_decode(side, q)
+    try:
+        kvm.kvm_set_option("decode.shared_tiles", shared_tiles)
+        got = gpu_decode(side, q)
+    finally:
+        kvm.kvm_set_option("decode.shared_tiles", 0)
     ref = oracle_decode(oracle, side, q)
     assert np.abs(got - ref).max() < TOL, np.abs(got - ref).max()
 

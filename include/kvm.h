@@ -247,17 +247,24 @@ const char* kvm_strerror(int status);
  * stays valid until the next failing call on this thread. */
 const char* kvm_last_error(void);
 /* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
- * value gives KVM_EINVAL.  Names: "copy.unroll" (1,2,4,8 16-byte vectors per
- * lane per workgroup pass, 0 = automatic), "copy.nontemporal" (0/1), "copy.order" (0: consecutive
- * workgroups walk the planes of one block; 1: plane outermost), "copy.lds_pad_kb"
- * (0..64: dynamic LDS per workgroup, caps residency), "copy.stage_linear" (bit 0:
- * kvm_pack, bit 1: kvm_unpack assign work in staging order, one 16-byte vector of
- * the staging buffer per lane; 0 = block-major work assignment as in kvm_migrate;
- * default 3), "decode.shared_tiles" (0/1, default 0: for grouped-query layouts,
- * 1 stages each K/V tile in LDS once per workgroup and gives every wave one query
- * head, 0 keeps the tile in one wave's registers for all heads of its group),
- * "decode.max_splits" (1..64), "decode.force_splits" (0 = automatic, else exactly
- * this many splits).
+ * value gives KVM_EINVAL.  Names:
+ *  "copy.unroll"        1,2,4,8 16-byte vectors per lane per workgroup; 0 = automatic (1).
+ *  "copy.nontemporal"   0/1 (default 1): streaming hint on loads and stores.
+ *  "copy.order"         1 (default): the (layer, K|V) plane is the outermost grid
+ *                       dimension; 0: consecutive workgroups walk the planes of one block.
+ *  "copy.lds_pad_kb"    0..64: dynamic LDS per workgroup, only caps residency.
+ *  "copy.stage_linear"  bit 0: kvm_pack, bit 1: kvm_unpack assign work in staging
+ *                       order (one 4 KiB piece of the staging buffer per workgroup)
+ *                       instead of by pool block; default 1.
+ *  "copy.stage_scalar_ids" 0/1 (default 1): where every workgroup of the
+ *                       staging-order kernels stays inside one block, its block id is
+ *                       one scalar load instead of a per-lane load.
+ *  "decode.shared_tiles" 0/1 (default 0): for grouped-query layouts, 1 stages each
+ *                       K/V tile in LDS once per workgroup and gives every wave one
+ *                       query head, 0 keeps the tile in one wave's registers for all
+ *                       heads of its group.
+ *  "decode.max_splits"  1..64.
+ *  "decode.force_splits" 0 = automatic, else exactly this many context splits.
  * Process-wide; not thread-safe against concurrent launches. */
 int kvm_set_option(const char* name, int64_t value);
 

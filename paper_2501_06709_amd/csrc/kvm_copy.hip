@@ -7,9 +7,10 @@
 //
 // All three operations are one kernel, `copy_kernel<MODE, U, NT>`:
 //  - a work item is (block entry of a request, plane = layer*2+kv, chunk); one
-//    256-lane workgroup moves up to U*256 16-byte vectors of it;
-//  - every lane issues its U loads before its first store, so a workgroup keeps
-//    U*4 KiB in flight; with 8 workgroups per CU that is 256 KiB per CU at U=8;
+//    256-lane workgroup moves up to U*256 16-byte vectors of it (U = 1 ships:
+//    4 KiB per workgroup, plane outermost in the grid);
+//  - every lane issues its U loads before its first store;
+//  - loads and stores carry the streaming (non-temporal) hint;
 //  - block ids and request descriptors are wave-uniform: they are read with
 //    scalar loads from the kernel-argument segment and the block table, which
 //    broadcasts them to all lanes without a vector load or LDS;
@@ -19,6 +20,7 @@
 //    (head, slot, vector) decomposition of the lane's vector index.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 
@@ -41,13 +43,33 @@ struct PoolSide {
   uint32_t dense;         // 1: a full block is one contiguous run per plane
 };
 
+// Division of x < 2^31 by a fixed divisor d >= 1 through one widening multiply
+// (Granlund & Montgomery, "Division by invariant integers using multiplication",
+// the round-up multiplier): with l = ceil(log2 d) and m = ceil(2^(31+l) / d) < 2^32,
+// floor(x / d) = (x * m) >> (31 + l) for every x < 2^31.  Branch-free.
+struct FastDiv {
+  uint32_t d, m, sh;
+};
+static FastDiv make_fastdiv(uint32_t d) {
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  FastDiv f;
+  f.d = d;
+  f.m = (uint32_t)(((1ull << (31 + l)) + d - 1) / d);
+  f.sh = 31 + l;
+  return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t x, const FastDiv& f) {
+  return (uint32_t)(((uint64_t)x * f.m) >> f.sh);
+}
+
 struct CopyReq {
   int32_t src_bt;      // first table entry of the request on the source side
   int32_t dst_bt;      // ... on the destination side
   int32_t k;           // tokens [start, k) are moved
   int32_t start;
   int32_t first_item;  // index of the request's first moved block among the launch's items
-  int32_t pad;
+  int32_t jb;          // first moved block of the request: start / B
   int64_t stage_vec;   // staging offset of the request in 16-byte vectors
 };
 
@@ -61,29 +83,38 @@ struct CopyArgs {
   int32_t n_chunks;    // workgroup passes per (item, plane)
   int32_t H, B;
   uint32_t DV;         // 16-byte vectors per token row (head_dim*2/16)
-  int32_t dv_shift;    // log2(DV) or -1
+  FastDiv dvdiv;       // division by DV
   int32_t order;       // 0: planes of a block are consecutive workgroups; 1: plane outermost
+  // first_item of every request again, densely packed (unused entries INT32_MAX),
+  // for the binary search that finds the owner of an item
+  int32_t first_item[kMaxReqPerLaunch];
   CopyReq req[kMaxReqPerLaunch];
 };
 
-__device__ __forceinline__ v4u load16(const char* p, bool nt) {
+// The streaming hint is a template parameter on purpose: written as a run-time
+// choice between a hinted and a plain access of the same address, the two are
+// merged by the optimiser and the hint is lost.
+template <bool NT>
+__device__ __forceinline__ v4u load16(const char* p) {
   const v4u* q = reinterpret_cast<const v4u*>(p);
-  return nt ? __builtin_nontemporal_load(q) : *q;
+  if constexpr (NT) return __builtin_nontemporal_load(q);
+  else return *q;
 }
-__device__ __forceinline__ void store16(char* p, v4u v, bool nt) {
+template <bool NT>
+__device__ __forceinline__ void store16(char* p, v4u v) {
   v4u* q = reinterpret_cast<v4u*>(p);
-  if (nt)
-    __builtin_nontemporal_store(v, q);
-  else
-    *q = v;
+  if constexpr (NT) __builtin_nontemporal_store(v, q);
+  else *q = v;
 }
 
 template <int MODE, int U, bool NT>
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   // ---- decode the work item (all wave-uniform, no division) ----
-  // grid = (chunks, planes, block entries): consecutive workgroups walk the chunks
-  // of one (block, plane), then the planes of the block, then the next block.
-  // With order = 1 the last two are swapped (plane outermost), kept for comparison.
+  // order 1 (shipped): grid = (chunks, block entries, planes): consecutive
+  // workgroups walk the chunks of one (block, plane) run, then the batch's other
+  // blocks in the same plane, and only then move to the next plane.
+  // order 0: grid = (chunks, planes, block entries): the planes of one block are
+  // consecutive, kept for comparison.
   const uint32_t chunk = blockIdx.x;
   const uint32_t plane = a.order ? blockIdx.z : blockIdx.y;
   const uint32_t item = a.order ? blockIdx.y : blockIdx.z;
@@ -92,11 +123,10 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
 #pragma unroll
   for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
     const int t = r + s;
-    if (t < a.n_req && a.req[t].first_item <= (int32_t)item) r = t;
+    if (a.first_item[t] <= (int32_t)item) r = t;
   }
-  int32_t j = (int32_t)item - a.req[r].first_item;  // block of the request, counted from its first moved one
   const CopyReq rq = a.req[r];
-  j += rq.start / a.B;                          // logical block of the request
+  const int32_t j = (int32_t)item - rq.first_item + rq.jb;  // logical block of the request
   // slots [s0, s1) of this block hold tokens of [start, k)
   const int32_t lo = rq.start - j * a.B, hi = rq.k - j * a.B;
   const uint32_t s0 = lo > 0 ? (uint32_t)lo : 0u;
@@ -132,12 +162,12 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t v = min(v0 + u * 256u, v_last);
-      val[u] = load16(sbase + (uint64_t)v * 16u, NT);
+      val[u] = load16<NT>(sbase + (uint64_t)v * 16u);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t v = v0 + u * 256u;
-      if (v < n_vec) store16(dbase + (uint64_t)v * 16u, val[u], NT);
+      if (v < n_vec) store16<NT>(dbase + (uint64_t)v * 16u, val[u]);
     }
     return;
   }
@@ -159,7 +189,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
     const uint32_t v = min(v0 + u * 256u, v_last);
     const uint32_t h = v / per_head;
     const uint32_t w = v - h * per_head;  // slot*DV + dv
-    const uint32_t slot = a.dv_shift >= 0 ? (w >> a.dv_shift) : (w / a.DV);
+    const uint32_t slot = fastdiv(w, a.dvdiv);
     const uint32_t dv = w - slot * a.DV;
     soff[u] = h * a.src.stride_head + slot * a.src.stride_slot + dv * 16u;
     doff[u] = h * a.dst.stride_head + slot * a.dst.stride_slot + dv * 16u;
@@ -167,20 +197,13 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    val[u] = load16(MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u], NT);
+    val[u] = load16<NT>(MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u]);
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t v = v0 + u * 256u;
-    if (v < n_vec) store16(MODE == kPack ? stage_plane + shead[u] : dbase + doff[u], val[u], NT);
+    if (v < n_vec) store16<NT>(MODE == kPack ? stage_plane + shead[u] : dbase + doff[u], val[u]);
   }
-}
-
-static int ilog2_exact(uint32_t v) {
-  if (!v || (v & (v - 1))) return -1;
-  int s = 0;
-  while ((1u << s) != v) ++s;
-  return s;
 }
 
 static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
@@ -197,14 +220,13 @@ static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
   return s;
 }
 
-// 16-byte vectors per lane per workgroup.  The automatic choice is what measured
-// best on MI355X for 32 KiB..160 KiB block runs: 4 for the fused move, 1 for pack
-// (its 4 KiB staging runs favour small workgroup footprints), 8 for unpack.
+// 16-byte vectors per lane per workgroup.  One (4 KiB per workgroup) measured best
+// on MI355X for all three operations once the plane is the outermost grid
+// dimension; larger values remain for comparison.
 template <int MODE>
 static int pick_unroll() {
   const int u = options().copy_unroll;
-  if (u) return u;
-  return MODE == kMigrate ? 4 : (MODE == kPack ? 1 : 8);
+  return u ? u : 1;
 }
 
 template <int MODE>
@@ -252,7 +274,7 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   a.H = l.n_kv_heads;
   a.B = l.block_tokens;
   a.DV = (uint32_t)(l.head_dim * 2 / 16);
-  a.dv_shift = ilog2_exact(a.DV);
+  a.dvdiv = make_fastdiv(a.DV);
   a.order = options().copy_order;
   const int U = pick_unroll<MODE>();
   const int64_t vec_per_item = (int64_t)l.n_kv_heads * l.block_tokens * a.DV;
@@ -264,6 +286,7 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   while (r < view.n_req) {
     a.n_req = 0;
     a.n_items = 0;
+    for (int i = 0; i < kMaxReqPerLaunch; ++i) a.first_item[i] = INT32_MAX;
     const int64_t max_items = 65535;  // grid dimension limit for y and z
     while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
       const int32_t items_r = view.nb[r] - view.jb[r];
@@ -276,7 +299,9 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
       q.k = view.k[r];
       q.start = view.start[r];
       q.first_item = a.n_items;
+      q.jb = view.jb[r];
       q.stage_vec = stage_vec;
+      a.first_item[a.n_req - 1] = a.n_items;
       a.n_items += items_r;
       stage_vec += (int64_t)(view.k[r] - view.start[r]) * bpt_vec;
       ++r;
@@ -290,102 +315,122 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
 
 // ---- staging-linear pack / unpack -------------------------------------------
 // A second mapping for the staged path: the work is cut along the staging buffer
-// instead of along pool blocks.  One workgroup moves U*256 consecutive 16-byte
-// vectors of one (request, plane, head) run of the staging buffer, so consecutive
-// workgroups walk the staging buffer linearly and every workgroup touches one
-// contiguous staging range; the pool side is then a gather (pack) or scatter
-// (unpack) of token rows, each lane looking its block id up in the table.
-// Division of a 32-bit value by a fixed divisor d through one high multiply
-// (Granlund & Montgomery, "Division by invariant integers using multiplication"):
-// with l = ceil(log2 d) and m = floor(2^32 (2^l - d) / d) + 1,
-// floor(x / d) = (t + ((x - t) >> 1)) >> (l - 1), t = mulhi(x, m), for d > 1.
-struct FastDiv {
-  uint32_t d, m, sh;  // sh = l - 1; d = 1 is flagged by m = 0
-};
-static FastDiv make_fastdiv(uint32_t d) {
-  FastDiv f{d, 0, 0};
-  if (d <= 1) return f;
-  uint32_t l = 0;
-  while ((1ull << l) < d) ++l;
-  f.m = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
-  f.sh = l - 1;
-  return f;
-}
-__device__ __forceinline__ uint32_t fastdiv(uint32_t x, const FastDiv& f) {
-  if (f.m == 0) return x;
-  const uint32_t t = __umulhi(x, f.m);
-  return (t + ((x - t) >> 1)) >> f.sh;
-}
-
+// instead of along pool blocks.  One workgroup moves U pieces of 256 consecutive
+// 16-byte vectors of one (request, plane, head) run of the staging buffer; the
+// pool side is then a gather (pack) or scatter (unpack) of token rows.
+//
+// At 4 KiB per workgroup a wave moves 1 KiB, so a long scalar preamble shows (a
+// 370-instruction straight-line one ran at two thirds of the rate of the
+// 100-instruction one below):
+//  - consecutive workgroups walk the staging buffer linearly (request, plane,
+//    head, chunk): that order measured 10 % faster than one that walks the chunks
+//    of all requests for one (plane, head) before the next head;
+//  - the owning request is found by a binary search over a dense first_wg array
+//    in the kernel-argument segment: six dependent scalar loads that hit the
+//    scalar cache (a one-load search through a vector load and a ballot measured
+//    2 % slower: under streaming load the vector memory path has the longer
+//    queue); the two divisions that split the workgroup index into (plane, head,
+//    chunk) are branch-free multiplications;
+//  - FAST (the host checks the conditions): every 256-vector piece lies inside one
+//    block and is contiguous there, so the block id is one scalar load per piece
+//    and a lane's address is base + lane*16 on both sides.
 struct StageReq {
-  int32_t bt;         // first table entry of the request
-  int32_t start;      // first token moved
-  int32_t n_tok;      // tokens moved: k - start
-  FastDiv chunks;     // workgroups per (plane, head) run
-  int64_t first_wg;   // first workgroup of the request in this launch
-  int64_t stage_vec;  // staging offset of the request in 16-byte vectors
+  int32_t bt;            // first table entry of the request
+  int32_t start;         // first token moved
+  uint32_t n_vec;        // vectors of one (plane, head) run: (k - start) * DV
+  uint32_t first_wg;     // first workgroup of the request in this launch
+  int64_t stage_vec;     // staging offset of the request in 16-byte vectors
+  int32_t j_last;        // block that holds token k - 1
+  FastDiv chunks;        // workgroups per (plane, head) run
 };
 
 struct StageArgs {
   PoolSide pool;
   char* stage;
-  int32_t n_req;
-  int32_t n_planes;
   int32_t H, B;
   uint32_t DV;
-  int32_t dv_shift, b_shift;  // log2 of DV and B, or -1
-  FastDiv heads;              // division by H
+  uint32_t piece_tokens;  // tokens per 256-vector piece (FAST only)
+  FastDiv dvdiv, bdiv, heads;  // division by DV, B, H
+  uint32_t first_wg[kMaxReqPerLaunch];  // densely packed, unused entries UINT32_MAX
   StageReq req[kMaxReqPerLaunch];
 };
 
-template <bool PACK, int U, bool NT>
+template <bool PACK, int U, bool NT, bool FAST>
 __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
-  const int64_t wg = blockIdx.x;
+  const uint32_t wg = blockIdx.x;
+  // owning request: largest r with first_wg[r] <= wg (unused entries never compare true)
   int r = 0;
 #pragma unroll
   for (int s = kMaxReqPerLaunch / 2; s > 0; s >>= 1) {
     const int t = r + s;
-    if (t < a.n_req && a.req[t].first_wg <= wg) r = t;
+    if (a.first_wg[t] <= wg) r = t;
   }
   const StageReq rq = a.req[r];
-  const uint32_t local = (uint32_t)(wg - rq.first_wg);
-  const uint32_t run = fastdiv(local, rq.chunks);       // (plane, head) run of the request
+  const uint32_t local = wg - rq.first_wg;
+  const uint32_t run = fastdiv(local, rq.chunks);  // (plane, head) run of the request
   const uint32_t chunk = local - run * rq.chunks.d;
   const uint32_t plane = fastdiv(run, a.heads);
   const uint32_t h = run - plane * a.heads.d;
-  const uint32_t n_vec = (uint32_t)rq.n_tok * a.DV;  // vectors of this (plane, head) run
+  const uint32_t n_vec = rq.n_vec;
   const uint32_t x0 = chunk * (U * 256u) + threadIdx.x;
   const uint32_t x_last = n_vec - 1;
   char* pbase = a.pool.base + (uint64_t)(plane >> 1) * a.pool.stride_layer +
                 (uint64_t)(plane & 1) * a.pool.stride_kv + (uint64_t)h * a.pool.stride_head;
-  char* sbase = a.stage + ((uint64_t)rq.stage_vec + ((uint64_t)plane * a.H + h) * n_vec) * 16u;
+  char* sbase = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)(plane * (uint32_t)a.H + h) * n_vec) * 16u;
+
+  v4u val[U];
+  if constexpr (FAST) {
+    char* pp[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // a piece past the end of the run (last chunk only) is pointed at the last
+      // block of the request; its lanes load in bounds and store nothing
+      const uint32_t t = (uint32_t)rq.start + (chunk * U + u) * a.piece_tokens;
+      const uint32_t j = min(fastdiv(t, a.bdiv), (uint32_t)rq.j_last);
+      const int32_t blk = a.pool.bt[rq.bt + (int32_t)j];
+      const uint32_t slot = t - fastdiv(t, a.bdiv) * (uint32_t)a.B;
+      pp[u] = pbase + (uint64_t)blk * a.pool.stride_block + slot * a.pool.stride_slot;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t x = x0 + u * 256u;
+      // lanes past the end repeat the piece's first vector (in bounds on both sides)
+      const uint32_t off = x < n_vec ? threadIdx.x * 16u : 0u;
+      val[u] = load16<NT>(PACK ? pp[u] + off : sbase + (uint64_t)min(x, x_last) * 16u);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t x = x0 + u * 256u;
+      if (x < n_vec) store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp[u] + threadIdx.x * 16u, val[u]);
+    }
+    return;
+  }
 
   int32_t blk[U];
   uint32_t inner[U];  // byte offset of the lane's vector inside its block
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t x = min(x0 + u * 256u, x_last);  // lanes past the end repeat the last vector
-    const uint32_t tok = a.dv_shift >= 0 ? (x >> a.dv_shift) : (x / a.DV);
+    const uint32_t tok = fastdiv(x, a.dvdiv);
     const uint32_t dv = x - tok * a.DV;
     const uint32_t t = (uint32_t)rq.start + tok;
-    const uint32_t j = a.b_shift >= 0 ? (t >> a.b_shift) : (t / (uint32_t)a.B);
+    const uint32_t j = fastdiv(t, a.bdiv);
     const uint32_t slot = t - j * (uint32_t)a.B;
     blk[u] = a.pool.bt[rq.bt + (int32_t)j];
     inner[u] = slot * a.pool.stride_slot + dv * 16u;
   }
-  v4u val[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t x = min(x0 + u * 256u, x_last);
     const char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
-    val[u] = load16(PACK ? pp : sbase + (uint64_t)x * 16u, NT);
+    val[u] = load16<NT>(PACK ? pp : sbase + (uint64_t)x * 16u);
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t x = x0 + u * 256u;
     if (x < n_vec) {
       char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
-      store16(PACK ? sbase + (uint64_t)x * 16u : pp, val[u], NT);
+      store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp, val[u]);
     }
   }
 }
@@ -395,40 +440,50 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
                      hipStream_t stream) {
   const kvm_layout& l = pool->layout;
   const Options& o = options();
-  // one vector per lane measured best: the finer the workgroups, the more
-  // sequential the stream that reaches the staging buffer's DRAM pages
-  const int U = o.copy_unroll ? o.copy_unroll : 1;
+  const int U = o.copy_unroll ? std::min(o.copy_unroll, 4) : 1;  // pieces per workgroup: 1, 2 or 4
   StageArgs a;
   memset(&a, 0, sizeof a);
   a.pool = make_side(pool, b);
   a.stage = stage;
-  a.n_planes = 2 * l.n_layers;
   a.H = l.n_kv_heads;
   a.B = l.block_tokens;
   a.DV = (uint32_t)(l.head_dim * 2 / 16);
-  a.dv_shift = ilog2_exact(a.DV);
-  a.b_shift = ilog2_exact((uint32_t)a.B);
+  a.dvdiv = make_fastdiv(a.DV);
+  a.bdiv = make_fastdiv((uint32_t)a.B);
   a.heads = make_fastdiv((uint32_t)a.H);
+  const int n_planes = 2 * l.n_layers;
   const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;
+  // FAST: a 256-vector piece covers whole tokens, a block holds a whole number of
+  // pieces, the rows of a block's head are contiguous and every range starts on a
+  // block boundary.
+  bool fast = o.stage_scalar_ids && 256 % a.DV == 0 && ((int64_t)a.B * a.DV) % 256 == 0 &&
+              a.pool.stride_slot == a.DV * 16u;
+  for (int q = 0; q < view.n_req && fast; ++q) fast = view.start[q] % a.B == 0;
+  a.piece_tokens = fast ? 256u / a.DV : 0u;
   int64_t stage_vec = 0;
   int r = 0;
   while (r < view.n_req) {
-    a.n_req = 0;
+    int n = 0;
+    for (int i = 0; i < kMaxReqPerLaunch; ++i) a.first_wg[i] = UINT32_MAX;
     int64_t n_wg = 0;
-    while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
+    while (r < view.n_req && n < kMaxReqPerLaunch) {
       const int64_t n_tok = view.k[r] - view.start[r];
+      if (((int64_t)view.k[r] + 1) * a.DV > 0x7fffffff)
+        return fail(KVM_EINVAL, "a single request's (plane, head) run exceeds 2^31 vectors");
       const int64_t chunks = ceil_div(n_tok * a.DV, (int64_t)U * 256);
-      const int64_t wgs = chunks * a.n_planes * a.H;
+      const int64_t wgs = chunks * n_planes * a.H;
       if (wgs > 0x7fffffff) return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
       if (n_wg + wgs > 0x7fffffff) break;
       if (n_tok > 0) {  // requests that move nothing take no descriptor
-        StageReq& q = a.req[a.n_req++];
+        StageReq& q = a.req[n];
         q.bt = view.bt_off[r];
         q.start = view.start[r];
-        q.n_tok = (int32_t)n_tok;
-        q.chunks = make_fastdiv((uint32_t)chunks);
-        q.first_wg = n_wg;
+        q.n_vec = (uint32_t)(n_tok * a.DV);
+        q.first_wg = (uint32_t)n_wg;
         q.stage_vec = stage_vec;
+        q.j_last = (view.k[r] - 1) / a.B;
+        q.chunks = make_fastdiv((uint32_t)chunks);
+        a.first_wg[n++] = (uint32_t)n_wg;
         n_wg += wgs;
       }
       stage_vec += n_tok * bpt_vec;
@@ -436,23 +491,23 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
     }
     if (n_wg == 0) continue;
     const dim3 grid((uint32_t)n_wg), block(256);
-#define KVM_STAGE(UU, NT) hipLaunchKernelGGL((stage_kernel<PACK, UU, NT>), grid, block, 0, stream, a)
-    if (o.copy_nontemporal) {
-      switch (U) {
-        case 1: KVM_STAGE(1, true); break;
-        case 2: KVM_STAGE(2, true); break;
-        case 8: KVM_STAGE(8, true); break;
-        default: KVM_STAGE(4, true); break;
-      }
-    } else {
-      switch (U) {
-        case 1: KVM_STAGE(1, false); break;
-        case 2: KVM_STAGE(2, false); break;
-        case 8: KVM_STAGE(8, false); break;
-        default: KVM_STAGE(4, false); break;
-      }
+#define KVM_STAGE2(UU, NT)                                                                       \
+  do {                                                                                           \
+    if (fast) hipLaunchKernelGGL((stage_kernel<PACK, UU, NT, true>), grid, block, 0, stream, a); \
+    else hipLaunchKernelGGL((stage_kernel<PACK, UU, NT, false>), grid, block, 0, stream, a);     \
+  } while (0)
+#define KVM_STAGE(UU)                              \
+  do {                                             \
+    if (o.copy_nontemporal) KVM_STAGE2(UU, true);  \
+    else KVM_STAGE2(UU, false);                    \
+  } while (0)
+    switch (U) {
+      case 1: KVM_STAGE(1); break;
+      case 2: KVM_STAGE(2); break;
+      default: KVM_STAGE(4); break;
     }
 #undef KVM_STAGE
+#undef KVM_STAGE2
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
   }

@@ -763,12 +763,20 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
   const float sc = scale == 0.f ? 1.0f / std::sqrt((float)l.head_dim) : scale;
   a.scale_log2e = sc * 1.4426950408889634f;
 
+  // Longest context first: workgroups are dispatched in grid order, so the long
+  // requests start early and the short ones fill the tail of the launch.  Every
+  // request keeps its own reduction order, so results do not depend on this.
+  std::vector<int> order(v.n_req);
+  for (int r = 0; r < v.n_req; ++r) order[r] = r;
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return v.k[x] > v.k[y]; });
+
   for (int r0 = 0; r0 < v.n_req; r0 += kMaxReqPerLaunch) {
     const int n = std::min(kMaxReqPerLaunch, v.n_req - r0);
     for (int i = 0; i < n; ++i) {
-      a.req[i].bt = v.bt_off[r0 + i];
-      a.req[i].k = v.k[r0 + i];
-      a.req[i].row = r0 + i;
+      const int r = order[r0 + i];
+      a.req[i].bt = v.bt_off[r];
+      a.req[i].k = v.k[r];
+      a.req[i].row = r;
     }
     hipError_t e;
     const hipStream_t st = (hipStream_t)hip_stream;

@@ -348,6 +348,9 @@ int kvm_set_option(const char* name, int64_t value) {
   } else if (!strcmp(name, "copy.stage_linear")) {
     if (value < 0 || value > 3) return fail(KVM_EINVAL, "copy.stage_linear must be in [0,3]");
     o.stage_linear = (int)value;
+  } else if (!strcmp(name, "copy.stage_scalar_ids")) {
+    if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.stage_scalar_ids must be 0 or 1");
+    o.stage_scalar_ids = (int)value;
   } else if (!strcmp(name, "decode.shared_tiles")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "decode.shared_tiles must be 0 or 1");
     o.decode_shared_tiles = (int)value;

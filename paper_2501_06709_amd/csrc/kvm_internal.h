@@ -41,9 +41,10 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
 struct Options {
   int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
-  int copy_order = 0;         // 0: planes of a block consecutive (shipped); 1: plane outermost
+  int copy_order = 1;         // 1: plane outermost (shipped); 0: planes of a block consecutive
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
-  int stage_linear = 3;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
+  int stage_linear = 1;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
+  int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block
   int decode_shared_tiles = 0;  // 1: grouped-query decode stages the K/V tile in LDS, one wave per query head
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits

@@ -18,7 +18,7 @@ from gpu_util import (DEV, Side, csr, dev_table, make_pair, oracle_migrate, rand
                       to_host)
 
 pytestmark = pytest.mark.gpu
-DEFAULTS = (0, 1, 0)   # copy.unroll, copy.nontemporal, copy.order as the library ships
+DEFAULTS = (0, 1, 1)   # copy.unroll, copy.nontemporal, copy.order as the library ships
 
 
 def run_all_three(orc, src, dst):
@@ -293,5 +293,5 @@ def test_staging_linear_mapping(oracle, mode, unroll):
         src, dst = make_pair(m3, n, n, lens3, ks3, seed=65)
         run_all_three(oracle, src, dst)
     finally:
-        kvm.kvm_set_option("copy.stage_linear", 3)
+        kvm.kvm_set_option("copy.stage_linear", 1)    # as the library ships
         kvm.kvm_set_option("copy.unroll", DEFAULTS[0])

@@ -183,6 +183,17 @@ def bench_mixed(a, log):
     log("mixed arena %.1f GiB, %d requests, %d orders" % (sc.arena_bytes / 2**30, len(sc.requests),
                                                           len(sc.orders)))
     mig = Migrator(dev, max(len(r.table) for r in sc.requests))
+    # warm-up, untimed: one block of every model moved into a free block of its other
+    # half and one decode over it, so that the first timed order does not pay for
+    # loading the kernels; the block is handed back, no request's table changes
+    for mi, m in enumerate(sc.models):
+        rq = next(r for r in sc.requests if r.model == mi)
+        got = mig.move(rq.table[:1], min(rq.length, m.B), pools[mi][rq.half], pools[mi][1 - rq.half],
+                       min(rq.length, m.B), decode=(qs[mi], outs[mi], None, 0))
+        mig.drain()                                   # would release the source block ...
+        pools[mi][rq.half].free.reserve(rq.table[:1])  # ... which stays in use
+        pools[mi][1 - rq.half].free.free(got)
+    torch.cuda.synchronize()
     moved = skipped = blocks = 0
     nbytes = 0
     t0 = time.perf_counter()
@@ -200,14 +211,16 @@ def bench_mixed(a, log):
         moved += 1
         blocks += len(ids)
         nbytes += 2 * k * m.bytes_per_token
+    t_host = time.perf_counter() - t0
     mig.drain()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    log("host loop %.1f ms" % (t_host * 1e3))
     log("%d orders moved (%d skipped) in %.1f ms" % (moved, skipped, dt * 1e3))
     gbs = nbytes / dt / 1e9
     print(json.dumps({
         "metric": "KV migrate GB/s (read+write)", "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1,
-        "steps": moved, "warmup": 0, "ms_per_step": round(dt * 1e3 / max(moved, 1), 4),
+        "steps": moved, "warmup": len(sc.models), "ms_per_step": round(dt * 1e3 / max(moved, 1), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": "mixed", "arena_bytes": sc.arena_bytes, "requests": len(sc.requests),

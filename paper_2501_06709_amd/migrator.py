@@ -2,8 +2,8 @@
 
 An order moves tokens [0,k) of one request from its pool into another pool of the
 same model (arXiv 2501.06709, Sec. "Adaptive Request Migration"): pop the
-destination blocks from the destination free list, upload the new block table,
-enqueue kvm_migrate (and optionally kvm_paged_decode over the destination), and
+destination blocks from the destination free list, upload both block tables
+(one copy), enqueue kvm_migrate (and optionally kvm_paged_decode over the destination), and
 return the source blocks to the source free list only after the copy has
 finished ("Boundary Profiling": source memory is held until the transfer is
 complete).  Orders are enqueued back to back on one stream; the release of order
@@ -30,12 +30,13 @@ class DevicePool:
 
 
 class _Slot:
+    """Pinned and device table space for one order in flight: the source table at
+    [0, n_src), the destination table right behind it, so one copy uploads both."""
+
     def __init__(self, max_blocks, device):
-        self.src_pin = torch.empty(max_blocks, dtype=torch.int32, pin_memory=True)
-        self.dst_pin = torch.empty(max_blocks, dtype=torch.int32, pin_memory=True)
-        self.src_dev = torch.empty(max_blocks, dtype=torch.int32, device=device)
-        self.dst_dev = torch.empty(max_blocks, dtype=torch.int32, device=device)
-        self.event = torch.cuda.Event()
+        self.pin = torch.empty(2 * max_blocks, dtype=torch.int32, pin_memory=True)
+        self.dev = torch.empty(2 * max_blocks, dtype=torch.int32, device=device)
+        self.event = torch.cuda.Event()      # the order's kernels have finished
         self.pending = None  # (source DevicePool, source ids) awaiting release
 
 
@@ -76,14 +77,18 @@ class Migrator:
         ids = dst.free.alloc(nb)                      # KVM_ENOMEM leaves everything as it was
         st = torch.cuda.current_stream() if stream is None else stream
         n_src = len(table)
-        slot.src_pin.numpy()[:n_src] = table
-        slot.dst_pin.numpy()[:nb] = ids
+        pin = slot.pin.numpy()
+        pin[:n_src] = table
+        pin[n_src:n_src + nb] = ids
+        n_up = max(n_src + nb, 1)
+        # in-stream: an upload on a side stream with an event wait measured 15 us per
+        # order slower than the copy it hides
         with torch.cuda.stream(st):
-            slot.src_dev[:max(n_src, 1)].copy_(slot.src_pin[:max(n_src, 1)], non_blocking=True)
-            slot.dst_dev[:max(nb, 1)].copy_(slot.dst_pin[:max(nb, 1)], non_blocking=True)
+            slot.dev[:n_up].copy_(slot.pin[:n_up], non_blocking=True)
+        src_dev, dst_dev = slot.dev[:max(n_src, 1)], slot.dev[n_src:n_src + max(nb, 1)]
         ks = np.array([k], dtype=np.int32)
-        sb = kvm.Batch(np.array([0, n_src], np.int32), np.asarray(table, np.int32), ks, slot.src_dev)
-        db = kvm.Batch(np.array([0, nb], np.int32), ids, ks, slot.dst_dev)
+        sb = kvm.Batch(np.array([0, n_src], np.int32), np.asarray(table, np.int32), ks, src_dev)
+        db = kvm.Batch(np.array([0, nb], np.int32), ids, ks, dst_dev)
         try:
             kvm.kvm_migrate(src.pool, sb, dst.pool, db, stream=st)
             if decode is not None and k > 0:

@@ -29,6 +29,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 
 #include "kvm_internal.h"
 
@@ -172,7 +173,9 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   if (jb >= je) return;
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  // uniform over the wave; saying so keeps the block loop's control flow and the
+  // block address arithmetic on the scalar unit
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % LPT;
   const int row = lane / LPT;
   const int hq0 = (h * a.passes + pass) * G;  // first query head served here
@@ -229,7 +232,10 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   // Software pipeline with one K and one V register tile: K of the next block is
   // requested as soon as the scores of the current one are formed, V of the next
   // block as soon as the current V rows are accumulated, so a load is always in
-  // flight while the other tile is being consumed.
+  // flight while the other tile is being consumed.  Every iteration issues both
+  // tile loads unconditionally; after the last block they go to the wave's own
+  // query row (valid, aligned, cached), which keeps the loop free of the register
+  // copies a conditional load would need.
   // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, the other counters left at
   // their maximum).  The explicit waits below keep the compiler from draining all
   // loads at the top of every iteration: without them it cannot prove that the
@@ -237,52 +243,56 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
   // inside a rare branch) are ready, and inserts vmcnt(0) on the hot path.
   constexpr int kWaitAll = 0x0F70;
   constexpr int kWaitAllButTiles = 0x0F70 | (2 * NI);   // 2*NI <= 8 tile loads may stay in flight
-  if (n_it > 0) {
-    fetch_ids(0);
-    __builtin_amdgcn_s_waitcnt(kWaitAll);
-    load_k(0, kc);
-    load_v(0, vc);
-    __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
-  }
-  for (int it = 0; it < n_it; ++it) {
+  const char* dummy = reinterpret_cast<const char*>(
+      a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // D*2 >= 128 bytes, 16-byte aligned
+  auto load_tile = [&](bool real, const char* base, int it, v4u* td) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
+    const char* p = real ? base + blk * a.stride_block + lane_off : dummy + (uint32_t)sub * 16u;
+    const uint32_t step = real ? inst_off : 0u;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i * step));
+  };
+  // One block of the context.  MASKED handles a last block that is only partly
+  // context; full blocks take the mask-free instance.
+  auto step = [&](auto masked_tag, int it, int t_limit) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
     const bool more = it + 1 < n_it;
-    const int j = jb + wave + 4 * it;
-    const int t_limit = k - j * B;  // slots >= t_limit of this block are not context
-
     float s[NI][G];
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i])) * sc;
+      for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i]));
     __builtin_amdgcn_sched_barrier(0);
-    if (more) {
-      if (((it + 1) & 63) == 0) {
-        fetch_ids(it + 1);
-        __builtin_amdgcn_s_waitcnt(kWaitAll);           // once per 64 blocks of this wave
-      }
-      load_k(it + 1, kc);
+    if (more && ((it + 1) & 63) == 0) {
+      fetch_ids(it + 1);
+      __builtin_amdgcn_s_waitcnt(kWaitAll);             // once per 64 blocks of this wave
     }
+    load_tile(more, kbase, it + 1, kc);
     __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+      // raw scores; the softmax scale enters through the fused multiply-add in
+      // front of each exponential (m[] holds scaled maxima)
       float mx = m[g];
 #pragma unroll
       for (int i = 0; i < NI; ++i)
-        if (i * TPI + row < t_limit) mx = fmaxf(mx, s[i][g]);
+        if (!MASKED || i * TPI + row < t_limit) mx = fmaxf(mx, s[i][g] * sc);
       const float alpha = __builtin_amdgcn_exp2f(m[g] - mx);
       m[g] = mx;
       float add = 0.f;
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        s[i][g] = (i * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[i][g] - mx) : 0.f;
+        const float e = __builtin_amdgcn_exp2f(fmaf(s[i][g], sc, -mx));
+        s[i][g] = (!MASKED || i * TPI + row < t_limit) ? e : 0.f;
         add += s[i][g];
       }
       lsum[g] = lsum[g] * alpha + add;
 #pragma unroll
       for (int c = 0; c < 8; ++c) o[g][c] *= alpha;
     }
-    if (t_limit < B) {
+    if (MASKED) {
       // Slots past the context may hold anything (NaN patterns included): clear
       // their V rows so that a zero weight cannot turn them into NaN.
 #pragma unroll
@@ -299,8 +309,23 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
         for (int c = 0; c < 8; ++c) o[g][c] = fmaf(s[i][g], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more) load_v(it + 1, vc);
+    load_tile(more, vbase, it + 1, vc);
     __builtin_amdgcn_sched_barrier(0);
+  };
+  // Only the request's last block can be partly context, and it is the last
+  // iteration of the one wave that owns it: all other iterations run the mask-free
+  // instance in a loop of their own.
+  if (n_it > 0) {
+    fetch_ids(0);
+    __builtin_amdgcn_s_waitcnt(kWaitAll);
+    load_k(0, kc);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(0, vc);
+    __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
+    const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;  // context slots in this wave's last block
+    const int n_main = t_last < B ? n_it - 1 : n_it;
+    for (int it = 0; it < n_main; ++it) step(std::false_type{}, it, B);
+    if (n_main < n_it) step(std::true_type{}, n_main, t_last);
   }
 
   // ---- merge the NP states of the workgroup through LDS ----

@@ -142,7 +142,8 @@ int64_t kvm_pool_span_bytes(const kvm_layout* layout, int64_t n_blocks);
  * staging_dev: device, 16-byte aligned, staging_bytes >= kvm_staging_bytes().
  * Reads the pool and the table only; writes exactly kvm_staging_bytes() bytes.
  * KVM_EINVAL: NULL pointer, bad layout, k out of range, block id outside
- * [0,n_blocks) (when host ids are given), staging too small or misaligned. */
+ * [0,n_blocks) (when host ids are given), staging too small, misaligned or
+ * overlapping the pool's span. */
 int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
              int64_t staging_bytes, void* hip_stream);
 

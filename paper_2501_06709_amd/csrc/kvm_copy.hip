@@ -514,6 +514,13 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
   return KVM_OK;
 }
 
+// True if [p, p + n) and the pool's span share a byte.
+static bool overlaps_pool(const void* p, int64_t n, const kvm_pool* pool) {
+  const char* a0 = (const char*)p;
+  const char* b0 = (const char*)pool->base;
+  return n > 0 && a0 < b0 + kvm_pool_span_bytes(&pool->layout, pool->n_blocks) && b0 < a0 + n;
+}
+
 static bool same_shape(const kvm_layout& a, const kvm_layout& b) {
   return a.n_layers == b.n_layers && a.n_kv_heads == b.n_kv_heads && a.n_q_heads == b.n_q_heads &&
          a.head_dim == b.head_dim && a.block_tokens == b.block_tokens && a.dtype == b.dtype;
@@ -535,6 +542,8 @@ int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
   if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_pack: staging_dev is NULL");
   if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_pack: staging_dev is not 16-byte aligned");
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_pack: staging buffer too small");
+  if (overlaps_pool(staging_dev, need, src))
+    return fail(KVM_EINVAL, "kvm_pack: the staging buffer overlaps the pool");
   if (options().stage_linear & 1)
     return run_stage<true>(src, src_reqs, sv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kPack>(src, src_reqs, sv, src, src_reqs, sv, (char*)staging_dev,
@@ -551,6 +560,8 @@ int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* d
   if (need > 0 && !staging_dev) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is NULL");
   if ((uintptr_t)staging_dev % 16) return fail(KVM_EINVAL, "kvm_unpack: staging_dev is not 16-byte aligned");
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_unpack: staging buffer too small");
+  if (overlaps_pool(staging_dev, need, dst))
+    return fail(KVM_EINVAL, "kvm_unpack: the staging buffer overlaps the pool");
   if (options().stage_linear & 2)
     return run_stage<false>(dst, dst_reqs, dv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kUnpack>(dst, dst_reqs, dv, dst, dst_reqs, dv, (char*)staging_dev,

@@ -39,6 +39,10 @@ bool layout_ok(const kvm_layout* l, std::string* why) {
     if ((s * 2) % 16) return bad("a stride is not a multiple of 16 bytes");
   }
   if (l->stride_slot < l->head_dim) return bad("stride_slot is smaller than head_dim");
+  // the kernels keep a lane's offset inside one block in 32 bits (bytes)
+  const __int128 inner = (__int128)(l->n_kv_heads - 1) * l->stride_head +
+                         (__int128)(l->block_tokens - 1) * l->stride_slot + l->head_dim;
+  if (inner > INT32_MAX) return bad("one block spans more than 2^32 bytes of head and slot strides");
   return true;
 }
 

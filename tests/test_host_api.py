@@ -62,6 +62,13 @@ def test_layout_validation():
     lay = kvm.kvm_layout_canonical(2, 4, 4, 64, 16, "f16", 8)
     lay.stride_slot = 60
     assert kvm.kvm_bytes_per_token(lay) == -1 and kvm.kvm_pool_span_bytes(lay, 8) == -1
+    # a block whose head and slot strides span more than 2^32 bytes is refused
+    # (the kernels keep a lane's offset inside one block in 32 bits)
+    lay = kvm.kvm_layout_canonical(2, 4, 4, 64, 16, "f16", 8)
+    lay.stride_head = 1 << 30
+    assert kvm.kvm_bytes_per_token(lay) == -1
+    lay.stride_head = (1 << 29)            # 3 * 2^29 + ... elements: still below 2^31
+    assert kvm.kvm_bytes_per_token(lay) == 2 * 2 * 4 * 64 * 2
 
 
 def _pool(n_blocks=32, m=wl.TINY, base=FAKE):
@@ -103,6 +110,9 @@ def test_argument_errors_come_before_any_launch():
     assert "too small" in _einval(kvm.kvm_pack, src, ok_s, FAKE, need - 1)
     assert "aligned" in _einval(kvm.kvm_pack, src, ok_s, FAKE + 8, need)
     assert "NULL" in _einval(kvm.kvm_unpack, None, dst, ok_d, staging_bytes=need)
+    span = kvm.kvm_pool_span_bytes(src.layout, 32)
+    assert "overlaps" in _einval(kvm.kvm_pack, src, ok_s, FAKE + span - 16, need)
+    assert "overlaps" in _einval(kvm.kvm_unpack, FAKE + (1 << 32) - need + 16, dst, ok_d, staging_bytes=need)
     # pointers
     assert "base is NULL" in _einval(kvm.kvm_pack, _pool(base=None), ok_s, FAKE, big)
     assert "aligned" in _einval(kvm.kvm_pack, _pool(base=FAKE + 4), ok_s, FAKE, big)

@@ -260,6 +260,11 @@ const char* kvm_last_error(void);
  *  "copy.stage_scalar_ids" 0/1 (default 1): where every workgroup of the
  *                       staging-order kernels stays inside one block, its block id is
  *                       one scalar load instead of a per-lane load.
+ *  "decode.mfma"        0/1 (default 0): 1 forms the scores of groups of four query
+ *                       heads (head_dim 128, 16-token blocks) on the matrix cores.
+ *  "decode.cap_waves"   -1 (default): the tuned decode kernels run at most two waves
+ *                       per SIMD when the mean context per workgroup is 2048 tokens or
+ *                       more; 0 never, 1 always.
  *  "decode.shared_tiles" 0/1 (default 0): for grouped-query layouts, 1 stages each
  *                       K/V tile in LDS once per workgroup and gives every wave one
  *                       query head, 0 keeps the tile in one wave's registers for all

@@ -145,8 +145,52 @@ __device__ __forceinline__ float* ws_entry(float* ws, const DecArgs& a, int row,
   return ws + ((((int64_t)row * a.L + l) * a.Hq + hq) * a.n_splits + split) * (D + 2);
 }
 
-template <int D, int B, int G, bool BF16>
-__global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
+// Combines the NP online-softmax states a workgroup has left in LDS (running max
+// in the exp2 domain, running sum, unnormalised accumulator) in state order and
+// writes the result: the normalised output row, or, when the context is split,
+// the workspace entry of this split.
+template <int D, int G, int NP, bool BF16>
+__device__ __forceinline__ void reduce_states(const DecArgs& a, const DecReq& rq, int l, int hq0, int split,
+                                              const float (*s_m)[G], const float (*s_l)[G],
+                                              const float (*s_o)[G][D]) {
+  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+    const int g = idx / D, d = idx % D;
+    float mx = kNegBig;
+#pragma unroll
+    for (int pidx = 0; pidx < NP; ++pidx) mx = fmaxf(mx, s_m[pidx][g]);
+    float acc = 0.f, den = 0.f;
+#pragma unroll
+    for (int pidx = 0; pidx < NP; ++pidx) {
+      const float wgt = __builtin_amdgcn_exp2f(s_m[pidx][g] - mx);
+      acc = fmaf(s_o[pidx][g][d], wgt, acc);
+      den = fmaf(s_l[pidx][g], wgt, den);
+    }
+    const int hq = hq0 + g;
+    if (a.n_splits == 1) {
+      const float res = acc / den;
+      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
+      if (a.out_f32)
+        reinterpret_cast<float*>(a.out)[oi] = res;
+      else
+        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
+    } else {
+      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
+      e[d] = acc;
+      if (d == 0) {
+        e[D] = mx;
+        e[D + 1] = den;
+      }
+    }
+  }
+}
+
+// WMAX caps the waves per SIMD.  With long contexts the rate falls as more
+// workgroups stream concurrently (measured on MI355X, group 4, 7680 tokens: 6.4
+// TB/s at two waves per SIMD, 6.1 at three or four; MHA 6.65 at two, 6.4 at four),
+// with short ones (mean 550 tokens) the cap costs 11 % because set-up and merge
+// of a workgroup are no longer hidden; the host picks 2 or 8 by mean context.
+template <int D, int B, int G, bool BF16, int WMAX>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_kernel(const DecArgs a) {
   constexpr int LPT = D / 8;       // lanes per token row
   constexpr int TPI = 64 / LPT;    // token rows per load instruction
   constexpr int NI = B / TPI;      // load instructions per block and per K / V
@@ -341,35 +385,203 @@ __global__ __launch_bounds__(256) void decode_kernel(const DecArgs a) {
     dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-    const int g = idx / D, d = idx % D;
-    float mx = kNegBig;
+  reduce_states<D, G, NP, BF16>(a, rq, l, hq0, split, s_m, s_l, s_o);
+}
+
+// Grouped-query decode with the scores on the matrix cores (group of four query
+// heads, head_dim 128, 16-token blocks).  q.K^T of one block is a 16 x 4 x 128
+// contraction: four v_mfma_f32_16x16x32 with the K tile as the A operand (rows =
+// tokens) and the four query heads in the first four columns of the B operand
+// replace 64 dot instructions and 64 cross-lane additions of the vector version.
+// Lane layouts (checked on the device against a plain matrix product):
+//   A: lane x holds row x%16, k = 8*(x/16) .. +7      -> K[token x%16][32j + 8*(x/16) ..]
+//   B: lane x holds column x%16, k = 8*(x/16) .. +7   -> Q[head x%16][32j + 8*(x/16) ..]
+//   D: lane x holds rows 4*(x/16) .. +3 of column x%16 -> score[token 4*(x/16)+r][head x%16]
+// so lane (head, lane row) owns the scores of four consecutive tokens and keeps the
+// online-softmax state of that (head, lane row) pair.  The V tile is loaded so
+// that lane row `row` holds tokens 4*row .. 4*row+3 as well, 16 bytes of each per
+// lane; the four weights and the rescale factor of every head then travel from
+// lane (head, row) to the sixteen lanes of the row with ds_bpermute (no LDS memory
+// is touched) and P.V stays on the vector unit.  K is read in 64-byte pieces per
+// token and instruction (two instructions complete each 128-byte line).
+// WMAX as for decode_kernel (8B workload: 6.27 TB/s at two waves per SIMD, 6.08 at
+// three, 5.87 at four).
+template <int D, int B, int G, bool BF16, int WMAX>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma_kernel(const DecArgs a) {
+  static_assert(D == 128 && B == 16 && G == 4, "shape of the matrix-core variant");
+  constexpr int NP = 16;  // 4 waves x 4 lane rows
+  __shared__ float s_m[NP][G];
+  __shared__ float s_l[NP][G];
+  __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
+
+  const int pass = blockIdx.x % a.passes;
+  const int h = blockIdx.x / a.passes;
+  const int l = blockIdx.y;
+  const int r = blockIdx.z / a.n_splits;
+  const int split = blockIdx.z % a.n_splits;
+  const DecReq rq = a.req[r];
+  const int k = rq.k;
+  if (k <= 0) return;
+  const int nb = (k + B - 1) / B;
+  const int per = (nb + a.n_splits - 1) / a.n_splits;
+  const int jb = split * per;
+  const int je = min(nb, jb + per);
+  if (jb >= je) return;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sub = lane % 16;
+  const int row = lane / 16;
+  const int hq0 = (h * a.passes + pass) * G;
+
+  // B operand: dims 32j + 8*row .. +7 of head `sub`; columns >= G are zero
+  const uint16_t* qrow = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D;
+  v4u qb[4];
 #pragma unroll
-    for (int pidx = 0; pidx < NP; ++pidx) mx = fmaxf(mx, s_m[pidx][g]);
-    float acc = 0.f, den = 0.f;
+  for (int j = 0; j < 4; ++j) {
+    qb[j] = v4u{0u, 0u, 0u, 0u};
+    if (sub < G) qb[j] = *reinterpret_cast<const v4u*>(qrow + sub * D + 32 * j + 8 * row);
+  }
+  const float sc = a.scale_log2e;
+
+  float m = kNegBig, lsum = 0.f;  // state of (head sub, lane row); meaningful for sub < G
+  float o[G][8];
 #pragma unroll
-    for (int pidx = 0; pidx < NP; ++pidx) {
-      const float wgt = __builtin_amdgcn_exp2f(s_m[pidx][g] - mx);
-      acc = fmaf(s_o[pidx][g][d], wgt, acc);
-      den = fmaf(s_l[pidx][g], wgt, den);
-    }
-    const int hq = hq0 + g;
-    if (a.n_splits == 1) {
-      const float res = acc / den;
-      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
-      if (a.out_f32)
-        reinterpret_cast<float*>(a.out)[oi] = res;
-      else
-        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
-    } else {
-      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
-      e[d] = acc;
-      if (d == 0) {
-        e[D] = mx;
-        e[D + 1] = den;
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] = 0.f;
+
+  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head;
+  const char* vbase = kbase + a.stride_kv;
+  const uint32_t k_off = (uint32_t)sub * a.stride_slot + (uint32_t)row * 16u;       // + 64*j
+  const uint32_t v_off = (uint32_t)(4 * row) * a.stride_slot + (uint32_t)sub * 16u;  // + i*stride_slot
+  const char* dummy = reinterpret_cast<const char*>(qrow) + (uint32_t)sub * 16u;     // 256 valid bytes
+  const int bp_row = 16 * row * 4;  // ds_bpermute byte address of lane (head 0, this lane's row)
+
+  const int n_it = (je - jb - wave + 3) / 4;
+  v4u kc[4], vc[4];
+  int ids = 0;
+  auto fetch_ids = [&](int it0) {
+    const int j = jb + wave + 4 * (it0 + lane);
+    ids = j < je ? a.bt[rq.bt + j] : 0;
+  };
+  auto load_k = [&](bool real, int it) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
+    const char* p = real ? kbase + blk * a.stride_block + k_off : dummy;
+    const uint32_t stp = real ? 64u : 0u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      kc[j] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + j * stp));
+  };
+  auto load_v = [&](bool real, int it) {
+    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
+    const char* p = real ? vbase + blk * a.stride_block + v_off : dummy;
+    const uint32_t stp = real ? a.stride_slot : 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      vc[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i * stp));
+  };
+  constexpr int kWaitAll = 0x0F70;
+  constexpr int kWaitAllButTiles = 0x0F70 | 8;
+
+  auto step = [&](auto masked_tag, int it, int t_limit) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const bool more = it + 1 < n_it;
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (BF16) {
+        typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, kc[j]), __builtin_bit_cast(b8, qb[j]),
+                                                      acc, 0, 0, 0);
+      } else {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kc[j]), __builtin_bit_cast(h8, qb[j]),
+                                                     acc, 0, 0, 0);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (more && ((it + 1) & 63) == 0) {
+      fetch_ids(it + 1);
+      __builtin_amdgcn_s_waitcnt(kWaitAll);
+    }
+    load_k(more, it + 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // online softmax of (head sub, lane row) over tokens 4*row .. 4*row+3 of the block
+    float mx = m;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      if (!MASKED || 4 * row + t < t_limit) mx = fmaxf(mx, acc[t] * sc);
+    const float alpha = __builtin_amdgcn_exp2f(m - mx);
+    m = mx;
+    float p[4], add = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float e = __builtin_amdgcn_exp2f(fmaf(acc[t], sc, -mx));
+      p[t] = (!MASKED || 4 * row + t < t_limit) ? e : 0.f;
+      add += p[t];
+    }
+    lsum = lsum * alpha + add;
+    // weights and rescale factor of head g: from lane (g, row) to the whole lane row
+    float pw[G][4], al[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      al[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 4 * g, __builtin_bit_cast(int, alpha)));
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        pw[g][t] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 4 * g, __builtin_bit_cast(int, p[t])));
+    }
+    if (MASKED) {
+      // rows past the context may hold anything: clear them so that a zero weight
+      // cannot turn a NaN pattern into NaN
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (4 * row + i >= t_limit) vc[i] = v4u{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] *= al[g];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float vf[8];
+      widen8<BF16>(vc[i], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[g][i], vf[c], o[g][c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(more, it + 1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  if (n_it > 0) {
+    fetch_ids(0);
+    __builtin_amdgcn_s_waitcnt(kWaitAll);
+    load_k(true, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(true, 0);
+    __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);  // queries have arrived
+    const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;
+    const int n_main = t_last < B ? n_it - 1 : n_it;
+    for (int it = 0; it < n_main; ++it) step(std::false_type{}, it, B);
+    if (n_main < n_it) step(std::true_type{}, n_main, t_last);
   }
+
+  const int slot = wave * 4 + row;
+  if (sub < G) {
+    s_m[slot][sub] = m;
+    s_l[slot][sub] = lsum;
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
+    dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
+    dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
+  }
+  __syncthreads();
+  reduce_states<D, G, NP, BF16>(a, rq, l, hq0, split, s_m, s_l, s_o);
 }
 
 // Grouped-query variant with the K/V tile of a block staged in LDS and shared by
@@ -670,6 +882,7 @@ struct DecodePlan {
   int g_tile;    // query heads per workgroup (1, 2 or 4)
   int passes;    // workgroups per KV head
   int n_splits;
+  bool cap;      // long contexts: at most two waves per SIMD
 };
 
 static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
@@ -691,6 +904,7 @@ static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
     s = std::min(s, o.decode_max_splits);
   }
   p.n_splits = std::max(1, std::min(s, 64));
+  p.cap = false;
   return p;
 }
 
@@ -698,21 +912,33 @@ static int64_t ws_bytes_for(const kvm_layout& l, int n_req, int n_splits) {
   return (int64_t)n_req * l.n_layers * l.n_q_heads * n_splits * (l.head_dim + 2) * 4;
 }
 
-template <int D, int B, bool BF16>
-static hipError_t launch_decode(const DecArgs& a, const DecodePlan& p, int n_req, hipStream_t st) {
-  const dim3 grid(a.H * p.passes, a.L, n_req * p.n_splits);
+template <int D, int B, bool BF16, int WMAX>
+static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, hipStream_t st) {
   const bool shared = options().decode_shared_tiles != 0;
   switch (p.g_tile) {
     case 4:
+      if constexpr (D == 128 && B == 16) {
+        if (options().decode_mfma) {
+          hipLaunchKernelGGL((decode_mfma_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
+          break;
+        }
+      }
       if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
       break;
     case 2:
       if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a);
+      else hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16, WMAX>), grid, dim3(256), 0, st, a);
       break;
-    default: hipLaunchKernelGGL((decode_kernel<D, B, 1, BF16>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_kernel<D, B, 1, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
   }
+}
+
+template <int D, int B, bool BF16>
+static hipError_t launch_decode(const DecArgs& a, const DecodePlan& p, int n_req, hipStream_t st) {
+  const dim3 grid(a.H * p.passes, a.L, n_req * p.n_splits);
+  if (p.cap) launch_main<D, B, BF16, 2>(a, p, grid, st);
+  else launch_main<D, B, BF16, 8>(a, p, grid, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.n_splits == 1) return e;
   hipLaunchKernelGGL((merge_kernel<D, B, BF16>), dim3(a.Hq, a.L, n_req), dim3(D), 0, st, a);
@@ -765,6 +991,17 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
     int64_t fit = (workspace_dev && (uintptr_t)workspace_dev % 16 == 0) ? workspace_bytes / per_split : 0;
     if (fit < 2) fit = 1;
     p.n_splits = (int)std::min<int64_t>(p.n_splits, fit);
+  }
+
+  {
+    // long contexts: cap the waves per SIMD (mean of 128 blocks = 2048 tokens per
+    // workgroup and more; at 34 blocks the cap costs 11 %, at 60 it changes nothing,
+    // at 480 it gains 6 %); "decode.cap_waves" overrides (0 never, 1 always)
+    int64_t live = 0;
+    for (int r = 0; r < v.n_req; ++r) live += v.nb[r] > 0;
+    const int64_t mean_blocks = v.total_blocks / std::max<int64_t>(1, live * p.n_splits);
+    const int mode = options().decode_cap_waves;
+    p.cap = mode < 0 ? mean_blocks >= 128 : mode != 0;
   }
 
   DecArgs a;

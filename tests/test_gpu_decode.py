@@ -50,20 +50,29 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("shared_tiles", [1, 0], ids=["lds_tiles", "register_tiles"])
+VARIANTS = {"matrix_core_scores": (1, 0), "register_tiles": (0, 0), "lds_tiles": (0, 1)}
+
+
+def set_variant(name):
+    mfma, shared = VARIANTS[name]
+    kvm.kvm_set_option("decode.mfma", mfma)
+    kvm.kvm_set_option("decode.shared_tiles", shared)
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
 @pytest.mark.parametrize("m", SHAPES, ids=[s.name for s in SHAPES])
-def test_decode_matches_oracle(oracle, m, shared_tiles):
-    """Both grouped-query kernels (K/V tile shared through LDS, or per-wave register
-    tiles) and the MHA kernel against the fp64 oracle."""
+def test_decode_matches_oracle(oracle, m, variant):
+    """The grouped-query kernels (scores on the matrix cores; per-wave register
+    tiles; K/V tile shared through LDS) and the MHA kernel against the fp64 oracle."""
     lens = [1, 15, 16, 17, 100, 333, 64]
     src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=21, finite=True)
     side = Side(m, 64, src.host, src.tables, lens)
     q = wl.gen_q(21, m, len(lens))
     try:
-        kvm.kvm_set_option("decode.shared_tiles", shared_tiles)
+        set_variant(variant)
         got = gpu_decode(side, q)
     finally:
-        kvm.kvm_set_option("decode.shared_tiles", 0)
+        set_variant("register_tiles")    # as the library ships
     ref = oracle_decode(oracle, side, q)
     assert np.abs(got - ref).max() < TOL, np.abs(got - ref).max()
 
@@ -78,6 +87,29 @@ def test_decode_k0_rows_untouched_and_scale(oracle):
     ref = oracle_decode(oracle, side, q, scale=0.3)
     assert (got[1] == 7.0).all()
     assert np.abs(got[[0, 2]] - ref[[0, 2]]).max() < TOL
+
+
+@pytest.mark.parametrize("variant", ["matrix_core_scores", "register_tiles"])
+def test_capped_occupancy_instances_give_the_same_bits(oracle, variant):
+    """The kernels exist in two instances (at most two or eight waves per SIMD, chosen by
+    mean context length); they are the same arithmetic."""
+    outs = []
+    for m in (SHAPES[1], SHAPES[2]):
+        lens = [333, 17, 64]
+        src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=29, finite=True)
+        side = Side(m, 64, src.host, src.tables, lens)
+        q = wl.gen_q(29, m, len(lens))
+        ref = oracle_decode(oracle, side, q)
+        try:
+            set_variant(variant)
+            for cap in (0, 1):
+                kvm.kvm_set_option("decode.cap_waves", cap)
+                outs.append(gpu_decode(side, q))
+        finally:
+            kvm.kvm_set_option("decode.cap_waves", -1)
+            set_variant("register_tiles")
+        assert np.array_equal(outs[-1], outs[-2])
+        assert np.abs(outs[-1] - ref).max() < TOL
 
 
 @pytest.mark.parametrize("splits", [2, 3, 7, 64])

@@ -152,8 +152,9 @@ def cpu_baseline(w, src_mem, staging_bytes_per_token, n_sample, log):
 
 def bench_mixed(a, log):
     """Multi-LLM mixed pool: the seeded order stream run back to back on one stream
-    (allocation, table upload, fused migrate, decode over the destination, deferred
-    source release), host overhead included.  One step = one order."""
+    (allocation, table upload (one per 16 orders), fused migrate, decode over the
+    destination, deferred source release), host overhead included.  One step = one
+    order."""
     import numpy as np
     import torch
 
@@ -202,8 +203,10 @@ def bench_mixed(a, log):
         m = sc.models[rq.model]
         k = int(np.floor(u * rq.length))
         try:
-            ids = mig.move(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half],
-                           k, decode=(qs[rq.model], outs[rq.model], None, 0))
+            # staged: the tables of up to 16 orders travel in one upload, the orders
+            # themselves still run one after the other, each with its decode
+            ids = mig.stage(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half],
+                            k, decode=(qs[rq.model], outs[rq.model], None, 0))
         except kvm.KvmError:
             skipped += 1
             continue

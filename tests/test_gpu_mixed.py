@@ -105,6 +105,84 @@ def test_mixed_pool_shrunken_matches_oracle_everywhere(oracle):
             assert pools[mi][h].free.available() == o_free[mi][h].available()
 
 
+def test_staged_orders_share_one_upload(oracle):
+    """Orders staged in groups of five (one table upload per group), requests that
+    appear twice in a group included: every order's decode over its destination
+    matches the fp64 oracle on the request's logical content, every live request
+    ends with the bytes it started with, the free lists are the complement of the
+    live tables."""
+    sc = mixed.make(n_requests=48, n_orders=80, median=40, cap=150, models=mixed.small_models())
+    arena, pools = build_device(sc)
+    start = arena.cpu().numpy().view(np.uint16).copy()
+
+    def logical(rq, n_tok):
+        """[2L][H][n_tok][D] content of the request's first n_tok tokens, from the
+        arena as it was before any order, through the blocks the request started in."""
+        m = sc.models[rq.model]
+        n = sc.half_blocks[rq.model]
+        out = np.zeros((2 * m.L, m.H, n_tok, m.D), np.uint16)
+        for j in range(-(-n_tok // m.B)):
+            oh, ob = rq.origin[j]
+            off = sc.half_offset[rq.model][oh] // 2
+            planes = start[off:off + n * m.block_bytes // 2].reshape(2 * m.L, n, m.H, m.B, m.D)
+            ns = min(m.B, n_tok - j * m.B)
+            out[:, :, j * m.B:j * m.B + ns] = planes[:, ob, :, :ns]
+        return out
+
+    mig = Migrator(DEV, max(len(rq.table) for rq in sc.requests), depth=4, max_staged=5)
+    checks = []
+    moved = 0
+    for oi, (ri, u) in enumerate(sc.orders):
+        rq = sc.requests[ri]
+        m = sc.models[rq.model]
+        k = order_k(rq, u)
+        q = wl.gen_q(sc.seed + oi, m, 1)
+        q_dev = torch.from_numpy(q.view(np.int16)).to(DEV)
+        out = torch.zeros(q.shape, dtype=torch.float32, device=DEV)
+        try:
+            ids = mig.stage(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half], k,
+                            decode=(q_dev, out, None, 0))
+        except kvm.KvmError as e:
+            assert e.status == kvm.KVM_ENOMEM
+            continue
+        if k > 0:
+            checks.append((oi, rq, k, q, q_dev, out, logical(rq, k)))   # content now: origin shrinks later
+        rq.table, rq.length, rq.half = ids, k, 1 - rq.half
+        rq.origin = rq.origin[:len(ids)]
+        moved += 1
+    mig.drain()
+    torch.cuda.synchronize()
+    assert moved >= 60
+    for oi, rq, k, q, _, out, kv in checks:                   # kv: [2L][H][k][D]
+        m = sc.models[rq.model]
+        nb = -(-k // m.B)
+        pad = np.zeros((2 * m.L, m.H, nb * m.B, m.D), np.uint16)
+        pad[:, :, :k] = kv
+        # a contiguous one-request pool in the canonical layout [layer][kv][block][head][slot][dim]
+        pool = pad.reshape(m.L, 2, m.H, nb, m.B, m.D).transpose(0, 1, 3, 2, 4, 5).copy()
+        st = oracle.canonical_strides(m.L, m.H, m.D, m.B, nb)
+        ref = oracle.paged_decode(pool.reshape(-1), st, m.L, m.H, m.Hq, m.D, m.B, m.dtype, [0, nb],
+                                  np.arange(nb), [k], q)
+        err = np.abs(out.cpu().numpy() - ref).max()
+        assert err < TOL, (oi, err)
+    end = arena.cpu().numpy().view(np.uint16)
+    for rq in sc.requests:
+        if rq.length == 0:
+            continue
+        m = sc.models[rq.model]
+        n = sc.half_blocks[rq.model]
+        off = sc.half_offset[rq.model][rq.half] // 2
+        planes = end[off:off + n * m.block_bytes // 2].reshape(2 * m.L, n, m.H, m.B, m.D)
+        exp = logical(rq, rq.length)
+        for j in range(-(-rq.length // m.B)):
+            ns = min(m.B, rq.length - j * m.B)
+            assert np.array_equal(planes[:, int(rq.table[j]), :, :ns], exp[:, :, j * m.B:j * m.B + ns])
+    for mi in range(len(sc.models)):
+        for h in range(2):
+            live = sum(len(rq.table) for rq in sc.requests if rq.model == mi and rq.half == h)
+            assert pools[mi][h].free.available() == sc.half_blocks[mi] - live
+
+
 def region_checksums(arena, sc):
     out = {}
     for mi, m in enumerate(sc.models):

@@ -48,7 +48,9 @@ typedef enum { KVM_F16 = 0, KVM_BF16 = 1 } kvm_dtype;
  *               + h*stride_head + s*stride_slot + d)          bytes.
  * Strides are in elements, the dim stride is 1.  The same block id addresses
  * the block in every (layer, kv) plane.  Required: head_dim*2 and every
- * stride*2 are multiples of 16 bytes; n_q_heads is a multiple of n_kv_heads.
+ * stride*2 are multiples of 16 bytes; n_q_heads is a multiple of n_kv_heads;
+ * stride_slot >= head_dim; (n_kv_heads-1)*stride_head + (block_tokens-1)*
+ * stride_slot + head_dim < 2^31 (a block's own extent fits 32 bits of bytes).
  */
 typedef struct {
   int32_t n_layers;
@@ -136,6 +138,10 @@ int64_t kvm_pool_span_bytes(const kvm_layout* layout, int64_t n_blocks);
  * append-only cache allows): with batch.start set, each call moves only
  * [start[r], k[r]); moving [0,a) and later [a,b) leaves the destination exactly
  * as moving [0,b) at once.
+ *
+ * Limits: a single request may move at most 65535 blocks in one call (a range
+ * [start,k) splits longer moves); batches of any size are split into launches
+ * of 64 requests internally.
  */
 
 /* Gather: staging[...] = src pool contents of tokens [0,k[r]) of each request.

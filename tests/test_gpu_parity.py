@@ -284,6 +284,15 @@ def test_staging_linear_mapping(oracle, mode, unroll):
         src, dst = make_pair(m2, 30, 30, [50, 12, 25], [41, 12, 13], seed=63, src_strides=tm,
                              start=[5, 0, 12])
         run_all_three(oracle, src, dst)
+        # shapes on both sides of the one-block-per-piece condition of the staging-order
+        # kernels: head_dim 256 (half a block per 4 KiB piece), 32-token blocks (two
+        # pieces per block), 8-token blocks (a piece spans two blocks: per-lane ids)
+        for mm, nblk in ((wl.Model("sl4", 1, 2, 2, 256, 16, "f16"), 24), (wl.Model("sl5", 2, 2, 2, 128, 32, "bf16"), 16),
+                         (wl.Model("sl6", 1, 3, 3, 128, 8, "f16"), 60)):
+            lens4 = [5 * mm.B, 3 * mm.B + 1, mm.B - 1, 2 * mm.B]
+            ks4 = [5 * mm.B, 2 * mm.B + 7, mm.B - 1, 2 * mm.B]
+            src, dst = make_pair(mm, nblk, nblk, lens4, ks4, seed=66)
+            run_all_three(oracle, src, dst)
         # more requests than one launch carries, some moving nothing
         m3 = wl.Model("sl3", 1, 2, 2, 64, 16, "f16")
         rng = np.random.default_rng(64)

@@ -91,21 +91,55 @@ struct CopyArgs {
   CopyReq req[kMaxReqPerLaunch];
 };
 
-// The streaming hint is a template parameter on purpose: written as a run-time
-// choice between a hinted and a plain access of the same address, the two are
-// merged by the optimiser and the hint is lost.
-template <bool NT>
-__device__ __forceinline__ v4u load16(const char* p) {
-  const v4u* q = reinterpret_cast<const v4u*>(p);
-  if constexpr (NT) return __builtin_nontemporal_load(q);
-  else return *q;
+// Streaming accesses.  The hinted form carries the cache-policy bits "sc0 sc1 nt"
+// (system scope, non-temporal): against "nt" alone it measured +1 % on the fused
+// move and +5 % on pack, against plain accesses +8 % and more.  The compiler's
+// builtins only reach "nt", so the hinted accesses are written as instructions:
+// all U loads of a lane and the wait for them form ONE asm statement, so no
+// register of theirs can be read before its data has arrived, and the loads of a
+// lane still overlap.  The hint is a template parameter on purpose: written as
+// a run-time choice between a hinted and a plain access of one address, the two
+// are merged by the optimiser and the hint is lost.
+#define KVM_LD "global_load_dwordx4 %"
+#define KVM_POL ", off sc0 sc1 nt\n\t"
+template <bool NT, int U>
+__device__ __forceinline__ void load16xU(const char* const (&p)[U], v4u (&v)[U]) {
+  static_assert(U == 1 || U == 2 || U == 4 || U == 8, "vectors per lane");
+  if constexpr (!NT) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = *reinterpret_cast<const v4u*>(p[u]);
+  } else if constexpr (U == 1) {
+    asm volatile(KVM_LD "0, %1" KVM_POL "s_waitcnt vmcnt(0)" : "=&v"(v[0]) : "v"(p[0]) : "memory");
+  } else if constexpr (U == 2) {
+    asm volatile(KVM_LD "0, %2" KVM_POL KVM_LD "1, %3" KVM_POL "s_waitcnt vmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1])
+                 : "v"(p[0]), "v"(p[1])
+                 : "memory");
+  } else if constexpr (U == 4) {
+    asm volatile(KVM_LD "0, %4" KVM_POL KVM_LD "1, %5" KVM_POL KVM_LD "2, %6" KVM_POL KVM_LD "3, %7" KVM_POL
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+                 : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3])
+                 : "memory");
+  } else {
+    asm volatile(KVM_LD "0, %8" KVM_POL KVM_LD "1, %9" KVM_POL KVM_LD "2, %10" KVM_POL KVM_LD "3, %11" KVM_POL
+                 KVM_LD "4, %12" KVM_POL KVM_LD "5, %13" KVM_POL KVM_LD "6, %14" KVM_POL KVM_LD "7, %15" KVM_POL
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]),
+                   "=&v"(v[7])
+                 : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7])
+                 : "memory");
+  }
 }
+#undef KVM_LD
 template <bool NT>
 __device__ __forceinline__ void store16(char* p, v4u v) {
-  v4u* q = reinterpret_cast<v4u*>(p);
-  if constexpr (NT) __builtin_nontemporal_store(v, q);
-  else *q = v;
+  if constexpr (NT)
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+  else
+    *reinterpret_cast<v4u*>(p) = v;
 }
+#undef KVM_POL
 
 template <int MODE, int U, bool NT>
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
@@ -159,11 +193,10 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   v4u val[U];
   if (MODE == kMigrate && dense) {
     // one contiguous run on both sides
+    const char* lp[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t v = min(v0 + u * 256u, v_last);
-      val[u] = load16<NT>(sbase + (uint64_t)v * 16u);
-    }
+    for (int u = 0; u < U; ++u) lp[u] = sbase + (uint64_t)min(v0 + u * 256u, v_last) * 16u;
+    load16xU<NT, U>(lp, val);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t v = v0 + u * 256u;
@@ -195,10 +228,10 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
     doff[u] = h * a.dst.stride_head + slot * a.dst.stride_slot + dv * 16u;
     shead[u] = (uint64_t)h * stage_head + (uint64_t)w * 16u;
   }
+  const char* lp[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    val[u] = load16<NT>(MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u]);
-  }
+  for (int u = 0; u < U; ++u) lp[u] = MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u];
+  load16xU<NT, U>(lp, val);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t v = v0 + u * 256u;
@@ -391,13 +424,15 @@ __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
       const uint32_t slot = t - fastdiv(t, a.bdiv) * (uint32_t)a.B;
       pp[u] = pbase + (uint64_t)blk * a.pool.stride_block + slot * a.pool.stride_slot;
     }
+    const char* lp[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t x = x0 + u * 256u;
       // lanes past the end repeat the piece's first vector (in bounds on both sides)
       const uint32_t off = x < n_vec ? threadIdx.x * 16u : 0u;
-      val[u] = load16<NT>(PACK ? pp[u] + off : sbase + (uint64_t)min(x, x_last) * 16u);
+      lp[u] = PACK ? pp[u] + off : sbase + (uint64_t)min(x, x_last) * 16u;
     }
+    load16xU<NT, U>(lp, val);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t x = x0 + u * 256u;
@@ -419,12 +454,14 @@ __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
     blk[u] = a.pool.bt[rq.bt + (int32_t)j];
     inner[u] = slot * a.pool.stride_slot + dv * 16u;
   }
+  const char* lp[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t x = min(x0 + u * 256u, x_last);
     const char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
-    val[u] = load16<NT>(PACK ? pp : sbase + (uint64_t)x * 16u);
+    lp[u] = PACK ? pp : sbase + (uint64_t)x * 16u;
   }
+  load16xU<NT, U>(lp, val);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t x = x0 + u * 256u;

@@ -1,8 +1,8 @@
 """Properties of the generated gfx950 code that the measured rates depend on.
 
-The streaming (non-temporal) hint of the copy kernels is worth 2-10 % of their
-rate and has been lost once to an optimiser merge of a hinted and a plain access
-of the same address; nothing else would notice.  The test compiles the copy
+The streaming hint of the copy kernels (cache-policy bits "sc0 sc1 nt") is worth
+2-10 % of their rate and has been lost once to an optimiser merge of a hinted and
+a plain access of the same address; nothing else would notice.  The test compiles the copy
 kernels' own source to assembly text (no GPU needed) and checks the modifier on
 every 16-byte access of the instantiations the library ships.
 """
@@ -49,7 +49,7 @@ def wide_accesses(text):
 def test_shipped_copy_kernels_carry_the_streaming_hint(copy_asm, prefix):
     acc = wide_accesses(body(copy_asm, prefix))
     assert len(acc) >= 2
-    assert all(a.endswith(" nt") for a in acc), [a for a in acc if not a.endswith(" nt")]
+    assert all(a.endswith(" sc0 sc1 nt") for a in acc), [a for a in acc if not a.endswith(" sc0 sc1 nt")]
 
 
 def test_plain_instantiation_has_no_hint(copy_asm):

@@ -104,8 +104,13 @@ typedef unsigned int kvmw_v4u __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void plain_copy_kernel(const char* src, char* dst, uint64_t n_vec) {
   const uint64_t v = (uint64_t)blockIdx.x * 256u + threadIdx.x;
   if (v < n_vec) {
-    const kvmw_v4u x = __builtin_nontemporal_load(reinterpret_cast<const kvmw_v4u*>(src) + v);
-    __builtin_nontemporal_store(x, reinterpret_cast<kvmw_v4u*>(dst) + v);
+    // same cache-policy bits as the library's copy kernels, so that the reference
+    // is not handicapped
+    const kvmw_v4u* s = reinterpret_cast<const kvmw_v4u*>(src) + v;
+    kvmw_v4u* d = reinterpret_cast<kvmw_v4u*>(dst) + v;
+    kvmw_v4u x;
+    asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(x) : "v"(s) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(d), "v"(x) : "memory");
   }
 }
 

@@ -262,7 +262,8 @@ const char* kvm_last_error(void);
  *  "copy.lds_pad_kb"    0..64: dynamic LDS per workgroup, only caps residency.
  *  "copy.stage_linear"  bit 0: kvm_pack, bit 1: kvm_unpack assign work in staging
  *                       order (one 4 KiB piece of the staging buffer per workgroup)
- *                       instead of by pool block; default 1.
+ *                       instead of by pool block; -1 (default): kvm_pack does when
+ *                       the batch's mean request moves 4096 tokens or more.
  *  "copy.stage_scalar_ids" 0/1 (default 1): where every workgroup of the
  *                       staging-order kernels stays inside one block, its block id is
  *                       one scalar load instead of a per-lane load.

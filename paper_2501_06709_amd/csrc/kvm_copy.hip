@@ -581,7 +581,14 @@ int kvm_pack(const kvm_pool* src, const kvm_batch* src_reqs, void* staging_dev,
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_pack: staging buffer too small");
   if (overlaps_pool(staging_dev, need, src))
     return fail(KVM_EINVAL, "kvm_pack: the staging buffer overlaps the pool");
-  if (options().stage_linear & 1)
+  // Work cut along the staging buffer pays for long requests (13B shape, 32768
+  // tokens: 6.34 against 6.15 TB/s); for short ones the block-cut kernel is as fast
+  // or faster (7B shape, 550 tokens: 6.31 against 6.64).  Automatic: by mean length.
+  const int mode = options().stage_linear;
+  int64_t live = 0;
+  for (int r = 0; r < sv.n_req; ++r) live += sv.k[r] > sv.start[r];
+  const bool linear = mode < 0 ? sv.total_tokens >= 4096 * std::max<int64_t>(1, live) : (mode & 1) != 0;
+  if (linear)
     return run_stage<true>(src, src_reqs, sv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kPack>(src, src_reqs, sv, src, src_reqs, sv, (char*)staging_dev,
                          (hipStream_t)hip_stream);
@@ -599,7 +606,7 @@ int kvm_unpack(const void* staging_dev, int64_t staging_bytes, const kvm_pool* d
   if (staging_bytes < need) return fail(KVM_EINVAL, "kvm_unpack: staging buffer too small");
   if (overlaps_pool(staging_dev, need, dst))
     return fail(KVM_EINVAL, "kvm_unpack: the staging buffer overlaps the pool");
-  if (options().stage_linear & 2)
+  if (options().stage_linear > 0 && (options().stage_linear & 2))
     return run_stage<false>(dst, dst_reqs, dv, (char*)staging_dev, (hipStream_t)hip_stream);
   return run_copy<kUnpack>(dst, dst_reqs, dv, dst, dst_reqs, dv, (char*)staging_dev,
                            (hipStream_t)hip_stream);

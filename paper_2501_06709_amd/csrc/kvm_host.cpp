@@ -350,7 +350,7 @@ int kvm_set_option(const char* name, int64_t value) {
     if (value < 0 || value > 64) return fail(KVM_EINVAL, "copy.lds_pad_kb must be in [0,64]");
     o.copy_lds_pad_kb = (int)value;
   } else if (!strcmp(name, "copy.stage_linear")) {
-    if (value < 0 || value > 3) return fail(KVM_EINVAL, "copy.stage_linear must be in [0,3]");
+    if (value < -1 || value > 3) return fail(KVM_EINVAL, "copy.stage_linear must be in [-1,3]");
     o.stage_linear = (int)value;
   } else if (!strcmp(name, "copy.stage_scalar_ids")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.stage_scalar_ids must be 0 or 1");

@@ -43,7 +43,7 @@ struct Options {
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
   int copy_order = 1;         // 1: plane outermost (shipped); 0: planes of a block consecutive
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
-  int stage_linear = 1;       // bit 0: pack, bit 1: unpack use the staging-linear mapping
+  int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
   int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block
   int decode_cap_waves = -1;    // -1: by mean context length; 0 / 1: never / always cap at two waves per SIMD
   int decode_mfma = 0;          // group-of-4, head_dim 128 decode: scores on the matrix cores

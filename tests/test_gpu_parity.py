@@ -302,5 +302,5 @@ def test_staging_linear_mapping(oracle, mode, unroll):
         src, dst = make_pair(m3, n, n, lens3, ks3, seed=65)
         run_all_three(oracle, src, dst)
     finally:
-        kvm.kvm_set_option("copy.stage_linear", 1)    # as the library ships
+        kvm.kvm_set_option("copy.stage_linear", -1)    # as the library ships
         kvm.kvm_set_option("copy.unroll", DEFAULTS[0])

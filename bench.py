@@ -37,7 +37,7 @@ HBM_PEAK_GBS = 8000.0
 # plain copy kernel of known size in the same run); the counter summaries are in
 # profiles/kvm_migrate_llama3_8b_gqa_pmc_hbm.md.  Workloads without a measurement
 # report null.
-MEASURED_TRAFFIC_BYTES = {"llama3_8b_gqa": 7993957580}
+MEASURED_TRAFFIC_BYTES = {"llama3_8b_gqa": 7995046550}
 
 
 def parse():

@@ -314,6 +314,12 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   a.n_chunks = (int32_t)ceil_div(vec_per_item, (int64_t)U * 256);
   const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;  // vectors per token
 
+  // limits are checked for the whole batch before the first launch: an error
+  // must mean that no device byte was written
+  for (int q = 0; q < view.n_req; ++q)
+    if (view.nb[q] - view.jb[q] > 65535)
+      return fail(KVM_EINVAL, "a single request moves more than 65535 blocks in one call");
+
   int64_t stage_vec = 0;
   int r = 0;
   while (r < view.n_req) {
@@ -323,8 +329,6 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
     const int64_t max_items = 65535;  // grid dimension limit for y and z
     while (r < view.n_req && a.n_req < kMaxReqPerLaunch) {
       const int32_t items_r = view.nb[r] - view.jb[r];
-      if (items_r > max_items)
-        return fail(KVM_EINVAL, "a single request moves more than 65535 blocks in one call");
       if ((int64_t)a.n_items + items_r > max_items) break;
       CopyReq& q = a.req[a.n_req++];
       q.src_bt = sv.bt_off[r];
@@ -497,6 +501,15 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
               a.pool.stride_slot == a.DV * 16u;
   for (int q = 0; q < view.n_req && fast; ++q) fast = view.start[q] % a.B == 0;
   a.piece_tokens = fast ? 256u / a.DV : 0u;
+  // limits are checked for the whole batch before the first launch: an error
+  // must mean that no device byte was written
+  for (int q = 0; q < view.n_req; ++q) {
+    if (((int64_t)view.k[q] + 1) * a.DV > 0x7fffffff)
+      return fail(KVM_EINVAL, "a single request's (plane, head) run exceeds 2^31 vectors");
+    const int64_t chunks = ceil_div((int64_t)(view.k[q] - view.start[q]) * a.DV, (int64_t)U * 256);
+    if (chunks * n_planes * a.H > 0x7fffffff)
+      return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
+  }
   int64_t stage_vec = 0;
   int r = 0;
   while (r < view.n_req) {
@@ -505,11 +518,8 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
     int64_t n_wg = 0;
     while (r < view.n_req && n < kMaxReqPerLaunch) {
       const int64_t n_tok = view.k[r] - view.start[r];
-      if (((int64_t)view.k[r] + 1) * a.DV > 0x7fffffff)
-        return fail(KVM_EINVAL, "a single request's (plane, head) run exceeds 2^31 vectors");
       const int64_t chunks = ceil_div(n_tok * a.DV, (int64_t)U * 256);
       const int64_t wgs = chunks * n_planes * a.H;
-      if (wgs > 0x7fffffff) return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
       if (n_wg + wgs > 0x7fffffff) break;
       if (n_tok > 0) {  // requests that move nothing take no descriptor
         StageReq& q = a.req[n];

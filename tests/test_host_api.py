@@ -203,3 +203,18 @@ def test_options_and_strerror():
             kvm.kvm_set_option(name, val)
     kvm.kvm_set_option("copy.unroll", 0)
     kvm.kvm_set_option("decode.force_splits", 0)
+
+
+def test_per_request_limit_is_checked_before_the_first_launch():
+    """65 requests, the last one beyond the per-call block limit: the error must come
+    before the launch that would carry the first 64 (an error means nothing ran)."""
+    n_big = 65536
+    n_blocks = 64 + n_big
+    src, dst = _pool(n_blocks), _pool(n_blocks, base=FAKE + (1 << 40))
+    off = np.concatenate([np.arange(65), [64 + n_big]]).astype(np.int32)
+    blk = np.arange(n_blocks, dtype=np.int32)
+    k = np.array([16] * 64 + [n_big * 16], np.int32)
+    b_s = kvm.Batch(off, blk, k, FAKE)
+    b_d = kvm.Batch(off, blk, k, FAKE)
+    assert "65535" in _einval(kvm.kvm_migrate, src, b_s, dst, b_d)
+    assert "65535" in _einval(kvm.kvm_unpack, FAKE + (1 << 41), dst, b_d, staging_bytes=1 << 40)

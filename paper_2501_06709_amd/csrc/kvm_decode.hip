@@ -145,6 +145,30 @@ __device__ __forceinline__ float* ws_entry(float* ws, const DecArgs& a, int row,
   return ws + ((((int64_t)row * a.L + l) * a.Hq + hq) * a.n_splits + split) * (D + 2);
 }
 
+// What one workgroup of the tuned kernels works on: grid = (KV heads x passes,
+// layers, requests x splits); a split covers blocks [jb, je) of the context.
+struct WorkItem {
+  DecReq rq;
+  int h, l, split;  // KV head, layer, split index
+  int hq0;          // first query head served by this workgroup
+  int jb, je;       // block range; jb >= je: nothing to do
+};
+template <int B, int G>
+__device__ __forceinline__ WorkItem work_item(const DecArgs& a) {
+  WorkItem w;
+  const int pass = blockIdx.x % a.passes;
+  w.h = blockIdx.x / a.passes;
+  w.l = blockIdx.y;
+  w.split = blockIdx.z % a.n_splits;
+  w.rq = a.req[blockIdx.z / a.n_splits];
+  w.hq0 = (w.h * a.passes + pass) * G;
+  const int nb = (max(w.rq.k, 0) + B - 1) / B;
+  const int per = (nb + a.n_splits - 1) / a.n_splits;
+  w.jb = w.split * per;
+  w.je = min(nb, w.jb + per);
+  return w;
+}
+
 // Combines the NP online-softmax states a workgroup has left in LDS (running max
 // in the exp2 domain, running sum, unnormalised accumulator) in state order and
 // writes the result: the normalised output row, or, when the context is split,
@@ -202,19 +226,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   __shared__ float s_l[NP][G];
   __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
 
-  const int pass = blockIdx.x % a.passes;
-  const int h = blockIdx.x / a.passes;
-  const int l = blockIdx.y;
-  const int r = blockIdx.z / a.n_splits;
-  const int split = blockIdx.z % a.n_splits;
-  const DecReq rq = a.req[r];
-  const int k = rq.k;
-  if (k <= 0) return;
-  const int nb = (k + B - 1) / B;
-  const int per = (nb + a.n_splits - 1) / a.n_splits;
-  const int jb = split * per;
-  const int je = min(nb, jb + per);
-  if (jb >= je) return;
+  const WorkItem wi = work_item<B, G>(a);
+  if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
+  const DecReq rq = wi.rq;
+  const int h = wi.h, l = wi.l, split = wi.split, k = rq.k, jb = wi.jb, je = wi.je;
 
   const int lane = threadIdx.x & 63;
   // uniform over the wave; saying so keeps the block loop's control flow and the
@@ -222,7 +237,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % LPT;
   const int row = lane / LPT;
-  const int hq0 = (h * a.passes + pass) * G;  // first query head served here
+  const int hq0 = wi.hq0;  // first query head served here
 
   // query fragment: dims sub*8 .. sub*8+7 of each of the G heads, kept as four
   // packed 16-bit pairs per head; the softmax scale is applied to the reduced score
@@ -414,25 +429,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   __shared__ float s_l[NP][G];
   __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
 
-  const int pass = blockIdx.x % a.passes;
-  const int h = blockIdx.x / a.passes;
-  const int l = blockIdx.y;
-  const int r = blockIdx.z / a.n_splits;
-  const int split = blockIdx.z % a.n_splits;
-  const DecReq rq = a.req[r];
-  const int k = rq.k;
-  if (k <= 0) return;
-  const int nb = (k + B - 1) / B;
-  const int per = (nb + a.n_splits - 1) / a.n_splits;
-  const int jb = split * per;
-  const int je = min(nb, jb + per);
-  if (jb >= je) return;
+  const WorkItem wi = work_item<B, G>(a);
+  if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
+  const DecReq rq = wi.rq;
+  const int h = wi.h, l = wi.l, split = wi.split, k = rq.k, jb = wi.jb, je = wi.je;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % 16;
   const int row = lane / 16;
-  const int hq0 = (h * a.passes + pass) * G;
+  const int hq0 = wi.hq0;
 
   // B operand: dims 32j + 8*row .. +7 of head `sub`; columns >= G are zero
   const uint16_t* qrow = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D;
@@ -613,19 +619,10 @@ __global__ __launch_bounds__(256) void decode_shared_kernel(const DecArgs a) {
   __shared__ float s_l[NP];
   __shared__ __attribute__((aligned(16))) float s_o[NP][D];
 
-  const int pass = blockIdx.x % a.passes;
-  const int h = blockIdx.x / a.passes;
-  const int l = blockIdx.y;
-  const int r = blockIdx.z / a.n_splits;
-  const int split = blockIdx.z % a.n_splits;
-  const DecReq rq = a.req[r];
-  const int k = rq.k;
-  if (k <= 0) return;
-  const int nb = (k + B - 1) / B;
-  const int per = (nb + a.n_splits - 1) / a.n_splits;
-  const int jb = split * per;
-  const int je = min(nb, jb + per);
-  if (jb >= je) return;
+  const WorkItem wi = work_item<B, G>(a);
+  if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
+  const DecReq rq = wi.rq;
+  const int h = wi.h, l = wi.l, split = wi.split, k = rq.k, jb = wi.jb, je = wi.je;
   const int n_it = je - jb;
 
   const int tid = threadIdx.x;
@@ -635,7 +632,7 @@ __global__ __launch_bounds__(256) void decode_shared_kernel(const DecArgs a) {
   const int row = lane / LPT;
   const int g = wave % G;          // query head of this wave
   const int part = wave / G;       // which row groups of the tile it takes
-  const int hq0 = (h * a.passes + pass) * G;
+  const int hq0 = wi.hq0;
 
   uint32_t qp[4];
   {

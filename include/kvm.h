@@ -257,8 +257,10 @@ const char* kvm_last_error(void);
  * value gives KVM_EINVAL.  Names:
  *  "copy.unroll"        1,2,4,8 16-byte vectors per lane per workgroup; 0 = automatic (1).
  *  "copy.nontemporal"   0/1 (default 1): streaming hint on loads and stores.
- *  "copy.order"         1 (default): the (layer, K|V) plane is the outermost grid
- *                       dimension; 0: consecutive workgroups walk the planes of one block.
+ *  "copy.order"         1: the (layer, K|V) plane is the outermost grid dimension;
+ *                       0: consecutive workgroups walk the planes of one block;
+ *                       -1 (default): 1 for layer-major pools (stride_kv >=
+ *                       stride_block) and for kvm_pack, 0 for block-major pools.
  *  "copy.lds_pad_kb"    0..64: dynamic LDS per workgroup, only caps residency.
  *  "copy.stage_linear"  bit 0: kvm_pack, bit 1: kvm_unpack assign work in staging
  *                       order (one 4 KiB piece of the staging buffer per workgroup)

@@ -308,7 +308,12 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   a.B = l.block_tokens;
   a.DV = (uint32_t)(l.head_dim * 2 / 16);
   a.dvdiv = make_fastdiv(a.DV);
-  a.order = options().copy_order;
+  // Workgroups walk the dimension with the smaller stride first: with layer-major
+  // pools (a plane spans all blocks) the plane is outermost, with block-major pools
+  // (a block's planes are adjacent) the planes of a block are consecutive.  Pack
+  // always takes the plane outermost: that is the order of its staging buffer.
+  a.order = options().copy_order >= 0 ? options().copy_order
+                                      : (MODE == kPack || l.stride_kv >= l.stride_block ? 1 : 0);
   const int U = pick_unroll<MODE>();
   const int64_t vec_per_item = (int64_t)l.n_kv_heads * l.block_tokens * a.DV;
   a.n_chunks = (int32_t)ceil_div(vec_per_item, (int64_t)U * 256);

@@ -344,7 +344,7 @@ int kvm_set_option(const char* name, int64_t value) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.nontemporal must be 0 or 1");
     o.copy_nontemporal = (int)value;
   } else if (!strcmp(name, "copy.order")) {
-    if (value < 0 || value > 1) return fail(KVM_EINVAL, "copy.order must be 0 or 1");
+    if (value < -1 || value > 1) return fail(KVM_EINVAL, "copy.order must be -1, 0 or 1");
     o.copy_order = (int)value;
   } else if (!strcmp(name, "copy.lds_pad_kb")) {
     if (value < 0 || value > 64) return fail(KVM_EINVAL, "copy.lds_pad_kb must be in [0,64]");

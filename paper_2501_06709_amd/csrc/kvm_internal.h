@@ -41,7 +41,7 @@ int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch
 struct Options {
   int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
-  int copy_order = 1;         // 1: plane outermost (shipped); 0: planes of a block consecutive
+  int copy_order = -1;        // -1: by layout (plane outermost for layer-major pools); 1: plane outermost; 0: planes of a block consecutive
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
   int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block

@@ -18,7 +18,7 @@ from gpu_util import (DEV, Side, csr, dev_table, make_pair, oracle_migrate, rand
                       to_host)
 
 pytestmark = pytest.mark.gpu
-DEFAULTS = (0, 1, 1)   # copy.unroll, copy.nontemporal, copy.order as the library ships
+DEFAULTS = (0, 1, -1)   # copy.unroll, copy.nontemporal, copy.order as the library ships
 
 
 def run_all_three(orc, src, dst):

@@ -14,10 +14,11 @@
 //  - block ids and request descriptors are wave-uniform: they are read with
 //    scalar loads from the kernel-argument segment and the block table, which
 //    broadcasts them to all lanes without a vector load or LDS;
-//  - a full block of the dense layout is one contiguous run per plane
-//    (heads*block_tokens*head_dim*2 bytes) and is moved with no index math
-//    beyond base + lane*16; partial last blocks and other layouts go through a
-//    (head, slot, vector) decomposition of the lane's vector index.
+//  - a full block of a dense layout (head-major or token-major rows) is one
+//    contiguous run per plane (heads*block_tokens*head_dim*2 bytes) and is moved
+//    with no index math beyond base + lane*16; partial last blocks of head-major
+//    blocks and other layouts go through a (head, slot, vector) decomposition of
+//    the lane's vector index.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -40,7 +41,7 @@ struct PoolSide {
   int64_t stride_block;
   uint32_t stride_head;   // bytes, within a block
   uint32_t stride_slot;
-  uint32_t dense;         // 1: a full block is one contiguous run per plane
+  uint32_t dense;         // a block is one contiguous run per plane: 1 head-major, 2 token-major rows; 0 neither
 };
 
 // Division of x < 2^31 by a fixed divisor d >= 1 through one widening multiply
@@ -169,18 +170,20 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
 
   const char* sbase = nullptr;
   char* dbase = nullptr;
-  bool dense = ns == (uint32_t)a.B;
+  // Fused fast path: the moved slots are one contiguous run on both sides and in
+  // the same order.  Head-major blocks ([head][slot][dim]): full blocks only.
+  // Token-major blocks ([slot][head][dim]): any slot range, its rows are adjacent.
+  bool dense = MODE == kMigrate && a.src.dense != 0 && a.src.dense == a.dst.dense &&
+               (a.src.dense == 2 || ns == (uint32_t)a.B);
   if (MODE != kUnpack) {
     const int64_t blk = a.src.bt[rq.src_bt + j];
     sbase = a.src.base + layer * a.src.stride_layer + kv * a.src.stride_kv + blk * a.src.stride_block +
             (uint64_t)s0 * a.src.stride_slot;
-    dense = dense && a.src.dense;
   }
   if (MODE != kPack) {
     const int64_t blk = a.dst.bt[rq.dst_bt + j];
     dbase = a.dst.base + layer * a.dst.stride_layer + kv * a.dst.stride_kv + blk * a.dst.stride_block +
             (uint64_t)s0 * a.dst.stride_slot;
-    dense = dense && a.dst.dense;
   }
   const uint32_t per_head = ns * a.DV;          // vectors per head in this item
   const uint32_t n_vec = per_head * (uint32_t)a.H;
@@ -249,7 +252,9 @@ static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
   s.stride_block = l.stride_block * 2;
   s.stride_head = (uint32_t)(l.stride_head * 2);
   s.stride_slot = (uint32_t)(l.stride_slot * 2);
-  s.dense = l.stride_slot == l.head_dim && l.stride_head == (int64_t)l.block_tokens * l.head_dim;
+  s.dense = 0;
+  if (l.stride_slot == l.head_dim && l.stride_head == (int64_t)l.block_tokens * l.head_dim) s.dense = 1;
+  else if (l.stride_head == l.head_dim && l.stride_slot == (int64_t)l.n_kv_heads * l.head_dim) s.dense = 2;
   return s;
 }
 

@@ -5,12 +5,13 @@
 // layer, K and V, are read through the source block table and written through
 // the destination block table (or to / from a contiguous staging buffer).
 //
-// All three operations are one kernel, `copy_kernel<MODE, U, NT>`:
+// All three operations are one kernel, `copy_kernel<MODE, U, NT>` (packing long
+// requests has a second one, `stage_kernel`, further down):
 //  - a work item is (block entry of a request, plane = layer*2+kv, chunk); one
 //    256-lane workgroup moves up to U*256 16-byte vectors of it (U = 1 ships:
 //    4 KiB per workgroup, plane outermost in the grid);
 //  - every lane issues its U loads before its first store;
-//  - loads and stores carry the streaming (non-temporal) hint;
+//  - loads and stores carry the streaming cache-policy bits (sc0 sc1 nt);
 //  - block ids and request descriptors are wave-uniform: they are read with
 //    scalar loads from the kernel-argument segment and the block table, which
 //    broadcasts them to all lanes without a vector load or LDS;

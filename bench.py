@@ -460,12 +460,16 @@ def main():
         "migrated_blocks_per_s": round(n_dst / (kern_ms["migrate"] * 1e-3), 1),
         "kernels": {
             "pack": {"ms": round(kern_ms["pack"], 4),
-                     "GB/s": round(2 * payload / kern_ms["pack"] / 1e6, 1)},
+                     "GB/s": round(2 * payload / kern_ms["pack"] / 1e6, 1),
+                     "frac_of_hbm_peak": round(2 * payload / kern_ms["pack"] / 1e6 / HBM_PEAK_GBS, 4)},
             "unpack": {"ms": round(kern_ms["unpack"], 4),
-                       "GB/s": round(2 * payload / kern_ms["unpack"] / 1e6, 1)},
-            "migrate": {"ms": round(kern_ms["migrate"], 4), "GB/s": round(mig_gbs, 1)},
+                       "GB/s": round(2 * payload / kern_ms["unpack"] / 1e6, 1),
+                       "frac_of_hbm_peak": round(2 * payload / kern_ms["unpack"] / 1e6 / HBM_PEAK_GBS, 4)},
+            "migrate": {"ms": round(kern_ms["migrate"], 4), "GB/s": round(mig_gbs, 1),
+                        "frac_of_hbm_peak": round(mig_gbs / HBM_PEAK_GBS, 4)},
             "decode": {"ms": round(kern_ms["decode"], 4),
-                       "GB/s": round(payload / kern_ms["decode"] / 1e6, 1)},
+                       "GB/s": round(payload / kern_ms["decode"] / 1e6, 1),
+                       "frac_of_hbm_peak": round(payload / kern_ms["decode"] / 1e6 / HBM_PEAK_GBS, 4)},
             "plain_copy": {"GB/s": round(memcpy_gbs, 1), "bytes": nb16},
         },
         "verified": verified,

@@ -271,6 +271,9 @@ const char* kvm_last_error(void);
  *                       one scalar load instead of a per-lane load.
  *  "decode.mfma"        0/1 (default 0): 1 forms the scores of groups of four query
  *                       heads (head_dim 128, 16-token blocks) on the matrix cores.
+ *  "decode.max_group"   8 (default) or 4: query heads of one KV head that a workgroup
+ *                       serves from one pass over K and V; a larger group takes
+ *                       several passes (reads K and V again).
  *  "decode.cap_waves"   -1 (default): the tuned decode kernels run at most two waves
  *                       per SIMD when the mean context per workgroup is 2048 tokens or
  *                       more; 0 never, 1 always.

@@ -222,9 +222,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   static_assert(LPT == 8 || LPT == 16, "head_dim must be 64 or 128");
   static_assert(B % TPI == 0, "block_tokens must be a multiple of the rows per load");
 
-  __shared__ float s_m[NP][G];
-  __shared__ float s_l[NP][G];
-  __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
+  constexpr int GS = G < 4 ? G : 4;  // heads merged through LDS at a time (33 KiB for D = 128)
+  __shared__ float s_m[NP][GS];
+  __shared__ float s_l[NP][GS];
+  __shared__ __attribute__((aligned(16))) float s_o[NP][GS][D];
 
   const WorkItem wi = work_item<B, G>(a);
   if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
@@ -387,20 +388,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
     if (n_main < n_it) step(std::true_type{}, n_main, t_last);
   }
 
-  // ---- merge the NP states of the workgroup through LDS ----
+  // ---- merge the NP states of the workgroup through LDS, GS heads at a time ----
   const int slot = wave * TPI + row;
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    if (sub == 0) {
-      s_m[slot][g] = m[g];
-      s_l[slot][g] = lsum[g];
+  for (int g0 = 0; g0 < G; g0 += GS) {
+    if (g0 > 0) __syncthreads();  // the previous group has been read
+#pragma unroll
+    for (int g = 0; g < GS; ++g) {
+      if (sub == 0) {
+        s_m[slot][g] = m[g0 + g];
+        s_l[slot][g] = lsum[g0 + g];
+      }
+      v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
+      dst[0] = v4f{o[g0 + g][0], o[g0 + g][1], o[g0 + g][2], o[g0 + g][3]};
+      dst[1] = v4f{o[g0 + g][4], o[g0 + g][5], o[g0 + g][6], o[g0 + g][7]};
     }
-    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
-    dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
-    dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
+    __syncthreads();
+    reduce_states<D, GS, NP, BF16>(a, rq, l, hq0 + g0, split, s_m, s_l, s_o);
   }
-  __syncthreads();
-  reduce_states<D, G, NP, BF16>(a, rq, l, hq0, split, s_m, s_l, s_o);
 }
 
 // Grouped-query decode with the scores on the matrix cores (group of four query
@@ -876,7 +881,7 @@ __global__ __launch_bounds__(64) void decode_generic_kernel(const DecArgs a, int
 }
 
 struct DecodePlan {
-  int g_tile;    // query heads per workgroup (1, 2 or 4)
+  int g_tile;    // query heads per workgroup (1, 2, 4 or 8)
   int passes;    // workgroups per KV head
   int n_splits;
   bool cap;      // long contexts: at most two waves per SIMD
@@ -885,7 +890,9 @@ struct DecodePlan {
 static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
   DecodePlan p;
   const int G = l.n_q_heads / l.n_kv_heads;
-  p.g_tile = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);
+  // eight query heads per KV head are served from one pass over K and V (two
+  // passes of four would read them twice)
+  p.g_tile = (G % 8 == 0 && options().decode_max_group >= 8) ? 8 : (G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1));
   p.passes = G / p.g_tile;
   const Options& o = options();
   int s = 1;
@@ -913,6 +920,7 @@ template <int D, int B, bool BF16, int WMAX>
 static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, hipStream_t st) {
   const bool shared = options().decode_shared_tiles != 0;
   switch (p.g_tile) {
+    case 8: hipLaunchKernelGGL((decode_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
     case 4:
       if constexpr (D == 128 && B == 16) {
         if (options().decode_mfma) {

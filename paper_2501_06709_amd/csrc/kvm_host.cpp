@@ -355,6 +355,9 @@ int kvm_set_option(const char* name, int64_t value) {
   } else if (!strcmp(name, "copy.stage_scalar_ids")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.stage_scalar_ids must be 0 or 1");
     o.stage_scalar_ids = (int)value;
+  } else if (!strcmp(name, "decode.max_group")) {
+    if (value != 4 && value != 8) return fail(KVM_EINVAL, "decode.max_group must be 4 or 8");
+    o.decode_max_group = (int)value;
   } else if (!strcmp(name, "decode.cap_waves")) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.cap_waves must be -1, 0 or 1");
     o.decode_cap_waves = (int)value;

@@ -45,6 +45,7 @@ struct Options {
   int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
   int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block
+  int decode_max_group = 8;     // largest number of query heads one workgroup serves from one pass over K/V (4 or 8)
   int decode_cap_waves = -1;    // -1: by mean context length; 0 / 1: never / always cap at two waves per SIMD
   int decode_mfma = 0;          // group-of-4, head_dim 128 decode: scores on the matrix cores
   int decode_shared_tiles = 0;  // 1: grouped-query decode stages the K/V tile in LDS, one wave per query head

@@ -269,8 +269,9 @@ const char* kvm_last_error(void);
  *  "copy.stage_scalar_ids" 0/1 (default 1): where every workgroup of the
  *                       staging-order kernels stays inside one block, its block id is
  *                       one scalar load instead of a per-lane load.
- *  "decode.mfma"        0/1 (default 0): 1 forms the scores of groups of four query
- *                       heads (head_dim 128, 16-token blocks) on the matrix cores.
+ *  "decode.mfma"        scores on the matrix cores (head_dim 128, 16-token blocks):
+ *                       -1 (default) for groups of eight query heads only, 0 never,
+ *                       1 for groups of four and eight.
  *  "decode.max_group"   8 (default) or 4: query heads of one KV head that a workgroup
  *                       serves from one pass over K and V; a larger group takes
  *                       several passes (reads K and V again).

@@ -428,11 +428,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 // three, 5.87 at four).
 template <int D, int B, int G, bool BF16, int WMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma_kernel(const DecArgs a) {
-  static_assert(D == 128 && B == 16 && G == 4, "shape of the matrix-core variant");
+  static_assert(D == 128 && B == 16 && (G == 4 || G == 8), "shape of the matrix-core variant");
   constexpr int NP = 16;  // 4 waves x 4 lane rows
-  __shared__ float s_m[NP][G];
-  __shared__ float s_l[NP][G];
-  __shared__ __attribute__((aligned(16))) float s_o[NP][G][D];
+  constexpr int GS = 4;   // heads merged through LDS at a time
+  __shared__ float s_m[NP][GS];
+  __shared__ float s_l[NP][GS];
+  __shared__ __attribute__((aligned(16))) float s_o[NP][GS][D];
 
   const WorkItem wi = work_item<B, G>(a);
   if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
@@ -581,18 +582,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   }
 
   const int slot = wave * 4 + row;
-  if (sub < G) {
-    s_m[slot][sub] = m;
-    s_l[slot][sub] = lsum;
-  }
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
-    dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
-    dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
+  for (int g0 = 0; g0 < G; g0 += GS) {
+    if (g0 > 0) __syncthreads();  // the previous group has been read
+    if (sub >= g0 && sub < g0 + GS) {
+      s_m[slot][sub - g0] = m;
+      s_l[slot][sub - g0] = lsum;
+    }
+#pragma unroll
+    for (int g = 0; g < GS; ++g) {
+      v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
+      dst[0] = v4f{o[g0 + g][0], o[g0 + g][1], o[g0 + g][2], o[g0 + g][3]};
+      dst[1] = v4f{o[g0 + g][4], o[g0 + g][5], o[g0 + g][6], o[g0 + g][7]};
+    }
+    __syncthreads();
+    reduce_states<D, GS, NP, BF16>(a, rq, l, hq0 + g0, split, s_m, s_l, s_o);
   }
-  __syncthreads();
-  reduce_states<D, G, NP, BF16>(a, rq, l, hq0, split, s_m, s_l, s_o);
 }
 
 // Grouped-query variant with the K/V tile of a block staged in LDS and shared by
@@ -920,10 +925,20 @@ template <int D, int B, bool BF16, int WMAX>
 static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, hipStream_t st) {
   const bool shared = options().decode_shared_tiles != 0;
   switch (p.g_tile) {
-    case 8: hipLaunchKernelGGL((decode_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
+    case 8:
+      // eight heads on the vector unit alone are bound by it (4.5 TB/s); with the
+      // scores on the matrix cores the kernel follows the stream again
+      if constexpr (D == 128 && B == 16) {
+        if (options().decode_mfma != 0) {
+          hipLaunchKernelGGL((decode_mfma_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a);
+          break;
+        }
+      }
+      hipLaunchKernelGGL((decode_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a);
+      break;
     case 4:
       if constexpr (D == 128 && B == 16) {
-        if (options().decode_mfma) {
+        if (options().decode_mfma > 0) {
           hipLaunchKernelGGL((decode_mfma_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
           break;
         }

@@ -362,7 +362,7 @@ int kvm_set_option(const char* name, int64_t value) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.cap_waves must be -1, 0 or 1");
     o.decode_cap_waves = (int)value;
   } else if (!strcmp(name, "decode.mfma")) {
-    if (value != 0 && value != 1) return fail(KVM_EINVAL, "decode.mfma must be 0 or 1");
+    if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.mfma must be -1, 0 or 1");
     o.decode_mfma = (int)value;
   } else if (!strcmp(name, "decode.shared_tiles")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "decode.shared_tiles must be 0 or 1");

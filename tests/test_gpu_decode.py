@@ -50,7 +50,7 @@ SHAPES = [
 ]
 
 
-VARIANTS = {"matrix_core_scores": (1, 0), "register_tiles": (0, 0), "lds_tiles": (0, 1)}
+VARIANTS = {"matrix_core_scores": (1, 0), "register_tiles": (0, 0), "lds_tiles": (0, 1), "shipped": (-1, 0)}
 
 
 def set_variant(name):
@@ -72,7 +72,7 @@ def test_decode_matches_oracle(oracle, m, variant):
         set_variant(variant)
         got = gpu_decode(side, q)
     finally:
-        set_variant("register_tiles")    # as the library ships
+        set_variant("shipped")
     ref = oracle_decode(oracle, side, q)
     assert np.abs(got - ref).max() < TOL, np.abs(got - ref).max()
 
@@ -107,7 +107,7 @@ def test_capped_occupancy_instances_give_the_same_bits(oracle, variant):
                 outs.append(gpu_decode(side, q))
         finally:
             kvm.kvm_set_option("decode.cap_waves", -1)
-            set_variant("register_tiles")
+            set_variant("shipped")
         assert np.array_equal(outs[-1], outs[-2])
         assert np.abs(outs[-1] - ref).max() < TOL
 

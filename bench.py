@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--order", type=int, default=None)
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--q-heads", type=int, default=None,
+                    help="query heads of the decode leg (a multiple of the KV heads); e.g. 64 on "
+                         "llama3_8b_gqa gives the 70B-class group of eight over the same KV")
     return ap.parse_args()
 
 
@@ -269,6 +272,10 @@ def main():
         % (free_b / 2**30, total_b / 2**30, w.name, payload / 2**30))
     # room beside the pools: staging for at least the largest request, tables, q, out
     w = fit_pools(w, free_b, int(w.k.max()) * m.bytes_per_token + (2 << 30), log)
+    if a.q_heads is not None:   # only the decode leg sees the query heads
+        import dataclasses
+        w.model = m = dataclasses.replace(w.model, Hq=a.q_heads)
+        w.notes = list(w.notes) + ["query heads overridden to %d" % a.q_heads]
     payload = w.payload_bytes()
 
     lay_s = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_src)

@@ -255,6 +255,7 @@ const char* kvm_strerror(int status);
 const char* kvm_last_error(void);
 /* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
  * value gives KVM_EINVAL.  Names:
+ *  "reset"              every option back to its default (the value is ignored).
  *  "copy.unroll"        1,2,4,8 16-byte vectors per lane per workgroup; 0 = automatic (1).
  *  "copy.nontemporal"   0/1 (default 1): streaming hint on loads and stores.
  *  "copy.order"         1: the (layer, K|V) plane is the outermost grid dimension;

@@ -336,7 +336,9 @@ const char* kvm_last_error(void) { return g_last_error.c_str(); }
 int kvm_set_option(const char* name, int64_t value) {
   if (!name) return fail(KVM_EINVAL, "kvm_set_option: name is NULL");
   Options& o = options();
-  if (!strcmp(name, "copy.unroll")) {
+  if (!strcmp(name, "reset")) {
+    o = Options();
+  } else if (!strcmp(name, "copy.unroll")) {
     if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
       return fail(KVM_EINVAL, "copy.unroll must be 0 (automatic), 1, 2, 4 or 8");
     o.copy_unroll = (int)value;

@@ -16,7 +16,6 @@ from test_gpu_parity import run_all_three
 pytestmark = pytest.mark.gpu
 
 OPTIONS = ("copy.unroll", "copy.order", "copy.stage_linear", "copy.stage_scalar_ids", "copy.nontemporal")
-SHIPPED = (0, -1, -1, 1, 1)
 
 
 def strides_for(rng, m, n_blocks):
@@ -64,13 +63,11 @@ def test_random_case(oracle, seed):
                              dst_strides=strides_for(rng, m, n_dst), start=start)
         run_all_three(oracle, src, dst)
     finally:
-        for name, v in zip(OPTIONS, SHIPPED):
-            kvm.kvm_set_option(name, v)
+        kvm.kvm_set_option("reset", 0)
     torch.cuda.synchronize()
 
 
 DEC_OPTIONS = ("decode.mfma", "decode.shared_tiles", "decode.cap_waves", "decode.force_splits")
-DEC_SHIPPED = (-1, 0, -1, 0)
 
 
 @pytest.mark.parametrize("seed", range(32))
@@ -94,7 +91,6 @@ def test_random_decode_case(oracle, seed):
         q = wl.gen_q(4000 + seed, m, n_req)
         got = gpu_decode(side, q)
     finally:
-        for name, v in zip(DEC_OPTIONS, DEC_SHIPPED):
-            kvm.kvm_set_option(name, v)
+        kvm.kvm_set_option("reset", 0)
     ref = oracle_decode(oracle, side, q)
     assert np.abs(got - ref).max() < 2e-3, (m, lens, values, np.abs(got - ref).max())

@@ -218,3 +218,14 @@ def test_per_request_limit_is_checked_before_the_first_launch():
     b_d = kvm.Batch(off, blk, k, FAKE)
     assert "65535" in _einval(kvm.kvm_migrate, src, b_s, dst, b_d)
     assert "65535" in _einval(kvm.kvm_unpack, FAKE + (1 << 41), dst, b_d, staging_bytes=1 << 40)
+
+
+def test_options_reset():
+    kvm.kvm_set_option("copy.unroll", 8)
+    kvm.kvm_set_option("decode.mfma", 1)
+    kvm.kvm_set_option("reset", 0)
+    # an out-of-range value is still refused, an unknown name too
+    for name, v in (("copy.unroll", 3), ("decode.max_group", 5), ("no.such.option", 1)):
+        with pytest.raises(kvm.KvmError) as e:
+            kvm.kvm_set_option(name, v)
+        assert e.value.status == kvm.KVM_EINVAL

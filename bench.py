@@ -51,6 +51,7 @@ def parse():
     ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--order", type=int, default=None)
+    ap.add_argument("--split-target", type=int, default=None)
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--q-heads", type=int, default=None,
                     help="query heads of the decode leg (a multiple of the KV heads); e.g. 64 on "
@@ -257,7 +258,7 @@ def main():
 
     kvm.lib()  # fails loudly if the HIP library is not built
     for name, val in (("copy.unroll", a.unroll), ("copy.nontemporal", a.nontemporal),
-                      ("copy.order", a.order)):
+                      ("copy.order", a.order), ("decode.split_target", a.split_target)):
         if val is not None:
             kvm.kvm_set_option(name, val)
     dev = torch.device("cuda:0")

@@ -283,6 +283,9 @@ const char* kvm_last_error(void);
  *                       K/V tile in LDS once per workgroup and gives every wave one
  *                       query head, 0 keeps the tile in one wave's registers for all
  *                       heads of its group.
+ *  "decode.split_target" workgroups a decode launch should reach by splitting
+ *                       contexts (default 2048; the mixed stream measures the same
+ *                       from 512 to 8192).
  *  "decode.max_splits"  1..64.
  *  "decode.force_splits" 0 = automatic, else exactly this many context splits.
  * Process-wide; not thread-safe against concurrent launches. */

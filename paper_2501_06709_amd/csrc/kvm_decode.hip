@@ -907,7 +907,7 @@ static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
     // Fill 256 CUs (x4 resident workgroups) when the batch alone cannot, but
     // keep at least 16 blocks (4 per wave) in every split.
     const int64_t base = (int64_t)n_req * l.n_layers * l.n_kv_heads * p.passes;
-    const int64_t want = base > 0 ? ceil_div(2048, base) : 1;
+    const int64_t want = base > 0 ? ceil_div(o.decode_split_target, base) : 1;
     const int64_t room = max_nb / 16;
     s = (int)std::max<int64_t>(1, std::min<int64_t>(want, room));
     s = std::min(s, o.decode_max_splits);

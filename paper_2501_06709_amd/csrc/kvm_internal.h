@@ -49,6 +49,7 @@ struct Options {
   int decode_cap_waves = -1;    // -1: by mean context length; 0 / 1: never / always cap at two waves per SIMD
   int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks): -1 groups of 8 only, 0 never, 1 groups of 4 and 8
   int decode_shared_tiles = 0;  // 1: grouped-query decode stages the K/V tile in LDS, one wave per query head
+  int decode_split_target = 2048;  // workgroups a decode launch should reach by splitting contexts
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits
 };

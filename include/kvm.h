@@ -196,6 +196,22 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
                      int64_t workspace_bytes, void* hip_stream);
 int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs);
 
+/* kvm_paged_decode for callers that cannot allocate device memory or pass a
+ * workspace along: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, checks, kernels and results as
+ * kvm_paged_decode, but the context-split workspace is a fixed array of
+ * KVM_STATIC_SCRATCH_BYTES that the library holds in device memory of every GPU
+ * it runs on (until the process ends); the call allocates nothing on the device.
+ * KVM_EINVAL (before any launch) when the batch's split workspace,
+ * kvm_decode_workspace_bytes(), exceeds KVM_STATIC_SCRATCH_BYTES; with default
+ * options no batch needs more than about 17 MiB.  KVM_EHIP when the array's
+ * device address cannot be obtained.  All calls on one GPU share the array:
+ * two calls may not overlap in time on one GPU (calls on one stream never do);
+ * nothing in it has to survive between calls and nothing needs clearing. */
+#define KVM_STATIC_SCRATCH_BYTES (32 << 20)
+int kvm_paged_decode_static(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev,
+                            void* out_dev, int out_is_f32, float scale, void* hip_stream);
+
 /* ---- host free-list allocator (integers only) ----------------------------
  * Destination blocks for a migrated request come from the destination pool's
  * free list (capacity constraint of Sec. "System Model", Eq. 2).  Lowest free

@@ -76,6 +76,9 @@ def lib():
         L.kvm_paged_decode.restype = ctypes.c_int
         L.kvm_paged_decode.argtypes = [P(kvm_pool), P(kvm_batch), VP, VP, ctypes.c_int,
                                        ctypes.c_float, VP, I64, VP]
+        L.kvm_paged_decode_static.restype = ctypes.c_int
+        L.kvm_paged_decode_static.argtypes = [P(kvm_pool), P(kvm_batch), VP, VP, ctypes.c_int,
+                                              ctypes.c_float, VP]
         L.kvm_decode_workspace_bytes.restype = I64
         L.kvm_decode_workspace_bytes.argtypes = [P(kvm_layout), P(kvm_batch)]
         L.kvm_freelist_create.restype = VP
@@ -211,6 +214,15 @@ def kvm_paged_decode(pool, reqs, q, out, out_is_f32=True, scale=0.0, workspace=N
     return _check(lib().kvm_paged_decode(ctypes.byref(pool.c), ctypes.byref(reqs.c), _devptr(q),
                                          _devptr(out), 1 if out_is_f32 else 0, scale,
                                          _devptr(workspace), workspace_bytes or 0, _stream(stream)))
+
+
+KVM_STATIC_SCRATCH_BYTES = 32 << 20  # as in kvm.h
+
+
+def kvm_paged_decode_static(pool, reqs, q, out, out_is_f32=True, scale=0.0, stream=None):
+    return _check(lib().kvm_paged_decode_static(ctypes.byref(pool.c), ctypes.byref(reqs.c), _devptr(q),
+                                                _devptr(out), 1 if out_is_f32 else 0, scale,
+                                                _stream(stream)))
 
 
 KVM_CLASS_KV, KVM_CLASS_TOKENS, KVM_CLASS_DEFER = 0, 1, 2

@@ -29,6 +29,8 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <string>
 #include <type_traits>
 
 #include "kvm_internal.h"
@@ -969,25 +971,51 @@ static hipError_t launch_decode(const DecArgs& a, const DecodePlan& p, int n_req
 
 using namespace kvm;
 
-extern "C" {
+// ---- static scratch of kvm_paged_decode_static -------------------------------
+// One file-scope device array per GPU (every device that loads the library holds
+// its own copy until the process ends) stands in for the caller's context-split
+// workspace.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device, with that
+// device current, and that pointer is what the kernels receive.
+// The split kernels write every workspace entry the merge kernel reads (a split
+// that sees no block is skipped by both), so nothing has to be cleared between
+// calls; calls that overlap in time on one GPU would share the entries and race.
+// No `used` attribute here: the compiler gives a static device variable that host
+// code names an externally visible device symbol, which is what the runtime looks
+// up; with the attribute the symbol stays local and the lookup cannot find it.
+static __device__ __align__(256) unsigned char scratch[KVM_STATIC_SCRATCH_BYTES];
 
-int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs) {
-  if (!layout_ok(layout, nullptr) || !reqs || reqs->n_req < 0 || (reqs->n_req > 0 && !reqs->k))
-    return -1;
-  int max_nb = 0;
-  for (int r = 0; r < reqs->n_req; ++r)
-    max_nb = std::max<int64_t>(max_nb, ceil_div(std::max(reqs->k[r], 0), layout->block_tokens));
-  const DecodePlan p = plan_decode(*layout, reqs->n_req, max_nb);
-  const bool tiled = layout->block_tokens == 16 && (layout->head_dim == 64 || layout->head_dim == 128);
-  return tiled && p.n_splits > 1 ? ws_bytes_for(*layout, reqs->n_req, p.n_splits) : 0;
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch`, per device
+
+static int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(KVM_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(KVM_EINVAL, "kvm_paged_decode_static: device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(KVM_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return KVM_OK;
 }
 
-int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
-                     int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
-                     void* hip_stream) {
+// Body of kvm_paged_decode and kvm_paged_decode_static.  With `static_scratch`
+// the context-split workspace is the library's own file-scope device array and
+// nothing is allocated; a plan whose workspace would not fit it is an error.
+static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
+                       int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
+                       bool static_scratch, void* hip_stream) {
   clear_error();
   BatchView v;
-  int rc = validate_side("kvm_paged_decode", pool, reqs, false, &v);
+  int rc = validate_side(static_scratch ? "kvm_paged_decode_static" : "kvm_paged_decode", pool, reqs,
+                         false, &v);
   if (rc) return rc;
   for (int r = 0; r < v.n_req; ++r)
     if (v.start[r] != 0) return fail(KVM_EINVAL, "kvm_paged_decode: reqs->start must be NULL or zero");
@@ -1005,6 +1033,21 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
   for (int r = 0; r < v.n_req; ++r) max_nb = std::max(max_nb, v.nb[r]);
   DecodePlan p = plan_decode(l, v.n_req, max_nb);
   if (!tiled) p.n_splits = 1;  // the fallback kernel does not split contexts
+  if (static_scratch && p.n_splits > 1) {
+    // the plan the automatic split count asks for must fit the static array
+    const int64_t need = ws_bytes_for(l, v.n_req, p.n_splits);
+    if (need > (int64_t)KVM_STATIC_SCRATCH_BYTES) {
+      char buf[160];
+      snprintf(buf, sizeof buf,
+               "kvm_paged_decode_static: the batch needs %lld bytes of split workspace, the static "
+               "scratch holds %lld",
+               (long long)need, (long long)KVM_STATIC_SCRATCH_BYTES);
+      return fail(KVM_EINVAL, buf);
+    }
+    rc = static_scratch_ptr(&workspace_dev);
+    if (rc) return rc;
+    workspace_bytes = KVM_STATIC_SCRATCH_BYTES;
+  }
   if (p.n_splits > 1) {
     // an absent or short workspace only limits how far the context is split
     const int64_t per_split = ws_bytes_for(l, v.n_req, 1);
@@ -1078,6 +1121,32 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
     if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
   }
   return KVM_OK;
+}
+
+extern "C" {
+
+int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs) {
+  if (!layout_ok(layout, nullptr) || !reqs || reqs->n_req < 0 || (reqs->n_req > 0 && !reqs->k))
+    return -1;
+  int max_nb = 0;
+  for (int r = 0; r < reqs->n_req; ++r)
+    max_nb = std::max<int64_t>(max_nb, ceil_div(std::max(reqs->k[r], 0), layout->block_tokens));
+  const DecodePlan p = plan_decode(*layout, reqs->n_req, max_nb);
+  const bool tiled = layout->block_tokens == 16 && (layout->head_dim == 64 || layout->head_dim == 128);
+  return tiled && p.n_splits > 1 ? ws_bytes_for(*layout, reqs->n_req, p.n_splits) : 0;
+}
+
+int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
+                     int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
+                     void* hip_stream) {
+  return decode_impl(pool, reqs, q_dev, out_dev, out_is_f32, scale, workspace_dev, workspace_bytes,
+                     /*static_scratch=*/false, hip_stream);
+}
+
+int kvm_paged_decode_static(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
+                            int out_is_f32, float scale, void* hip_stream) {
+  return decode_impl(pool, reqs, q_dev, out_dev, out_is_f32, scale, nullptr, 0, /*static_scratch=*/true,
+                     hip_stream);
 }
 
 }  // extern "C"

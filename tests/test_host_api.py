@@ -229,3 +229,25 @@ def test_options_reset():
         with pytest.raises(kvm.KvmError) as e:
             kvm.kvm_set_option(name, v)
         assert e.value.status == kvm.KVM_EINVAL
+
+
+def test_static_scratch_decode_rejects_a_plan_beyond_its_array():
+    """kvm_paged_decode_static refuses, before any HIP call, a batch whose split
+    workspace is larger than the static array; the constant matches the header."""
+    text = open(os.path.join(ROOT, "include", "kvm.h")).read()
+    mo = re.search(r"#define\s+KVM_STATIC_SCRATCH_BYTES\s+\((\d+)\s*<<\s*(\d+)\)", text)
+    assert mo and int(mo.group(1)) << int(mo.group(2)) == kvm.KVM_STATIC_SCRATCH_BYTES
+    m = wl.LLAMA3_8B
+    pool = _pool(16 * 1024, m=m)
+    off = (np.arange(17) * 1024).astype(np.int32)
+    batch = kvm.Batch(off, np.arange(16 * 1024, dtype=np.int32), [16384] * 16, FAKE)
+    try:
+        kvm.kvm_set_option("decode.force_splits", 64)
+        need = kvm.kvm_decode_workspace_bytes(pool.layout, batch)
+        assert need == 16 * m.L * m.Hq * 64 * (m.D + 2) * 4 > kvm.KVM_STATIC_SCRATCH_BYTES
+        detail = _einval(kvm.kvm_paged_decode_static, pool, batch, FAKE, FAKE)
+        assert str(need) in detail and str(kvm.KVM_STATIC_SCRATCH_BYTES) in detail
+    finally:
+        kvm.kvm_set_option("reset", 0)
+    # the same argument checks as kvm_paged_decode
+    assert "q_dev" in _einval(kvm.kvm_paged_decode_static, pool, batch, None, FAKE)

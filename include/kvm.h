@@ -196,6 +196,19 @@ int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_
                      int64_t workspace_bytes, void* hip_stream);
 int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* reqs);
 
+/* kvm_paged_decode with an explicit row per request: request r reads its query
+ * from row rows[r] of q_dev and writes row rows[r] of out_dev (rows: host,
+ * [n_req]; NULL = the identity, i.e. kvm_paged_decode).  This is what lets the
+ * requests that one time slot's migration orders moved into a pool (Sec. "Online KV
+ * Cache Scheduling", request operation batching: a slot's moves are known together)
+ * be decoded by ONE call although their queries sit in rows of a larger per-model
+ * query buffer.  Rows beyond the buffers are the caller's responsibility.
+ * KVM_EINVAL in addition to kvm_paged_decode's: a negative row, or two requests
+ * with k > 0 that share a row. */
+int kvm_paged_decode_rows(const kvm_pool* pool, const kvm_batch* reqs, const int32_t* rows,
+                          const void* q_dev, void* out_dev, int out_is_f32, float scale,
+                          void* workspace_dev, int64_t workspace_bytes, void* hip_stream);
+
 /* kvm_paged_decode for callers that cannot allocate device memory or pass a
  * workspace along: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, checks, kernels and results as

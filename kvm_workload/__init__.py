@@ -101,6 +101,24 @@ def gen_block(seed, stream, model, plane, block):
                       model.dtype).reshape(model.H, model.B, model.D)
 
 
+def gen_blocks(seed, stream, model, plane, blocks):
+    """Blocks `blocks` of one plane as uint16 [len(blocks)][H][B][D] (one vectorised
+    pass: for regenerating many blocks of a large pool on the host)."""
+    blocks = np.asarray(blocks, dtype=np.int64)
+    n = model.H * model.B * model.D
+    key = plane_key(seed, stream, plane)
+    with np.errstate(over="ignore"):
+        kb = mix32((np.uint32(key) + (blocks.astype(np.uint64) * _BLK).astype(np.uint32)))
+        x = mix32(kb[:, None] + np.arange(n, dtype=np.uint32)[None, :])
+        y = mix32(x ^ _YX)
+    s = np.zeros(x.shape, dtype=np.int32)
+    for sh in (0, 8, 16, 24):
+        s += ((x >> np.uint32(sh)) & np.uint32(0xFF)).astype(np.int32)
+        s += ((y >> np.uint32(sh)) & np.uint32(0xFF)).astype(np.int32)
+    f = (s - 1020).astype(np.float32) * INV_SD
+    return f32_to_bits16(f, model.dtype).reshape(len(blocks), model.H, model.B, model.D)
+
+
 def gen_pool_host(seed, stream, model, n_blocks, strides=None, blocks=None):
     """A whole pool on the host as a flat uint16 array (small pools only).
     `blocks`: only these ids are generated, the rest stays zero."""

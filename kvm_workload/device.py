@@ -30,6 +30,12 @@ def _load():
         _lib.kvmw_fill_pool.restype = ctypes.c_int
         _lib.kvmw_fill_pool.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 5 + [
             ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p]
+        _lib.kvmw_gen_blocks.restype = ctypes.c_int
+        _lib.kvmw_gen_blocks.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64] + [
+            ctypes.c_int] * 4 + [ctypes.c_uint32] * 3 + [ctypes.c_void_p]
+        _lib.kvmw_block_hashes.restype = ctypes.c_int
+        _lib.kvmw_block_hashes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         _lib.kvmw_plain_copy.restype = ctypes.c_int
         _lib.kvmw_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p]
@@ -59,14 +65,45 @@ def fill_pool(mem, model, n_blocks, seed, stream_id, strides=None, b0=0, b1=None
         raise RuntimeError("kvmw_fill_pool failed with %d" % rc)
 
 
-def plane_block_checksums(mem, model, n_blocks):
-    """Wrapping int64 sum of every (plane, block) of a dense pool -> [2L, n_blocks]
-    (torch reduction; used to show that blocks were left untouched)."""
+def gen_blocks(out, ids_dev, model, seed, stream_id, plane):
+    """out[i] <- generator content of block ids_dev[i] of `plane` (dense [H][B][D]
+    16-bit per block; `out` is a torch tensor of at least len(ids) blocks)."""
     import torch
+    n = int(ids_dev.numel())
+    assert ids_dev.dtype == torch.int32 and ids_dev.is_contiguous()
+    assert out.numel() * out.element_size() >= n * model.H * model.B * model.D * 2
+    rc = _load().kvmw_gen_blocks(out.data_ptr(), ids_dev.data_ptr(), n, model.H, model.B, model.D,
+                                 1 if model.dtype == "bf16" else 0, seed & 0xFFFFFFFF, stream_id,
+                                 plane, torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("kvmw_gen_blocks failed with %d" % rc)
+
+
+MIX64_GOLD = 0x9E3779B97F4A7C15
+
+
+def plane_block_hashes(mem, model, n_blocks):
+    """Position-sensitive 64-bit hash of every (plane, block) of a dense canonical
+    pool -> int64 tensor [2L, n_blocks]: sum over the block's 8-byte words of
+    splitmix64(word + (index + 1) * 0x9E3779B97F4A7C15), mod 2^64.  Used to show that
+    blocks were left untouched; unlike a plain sum it sees words that moved."""
+    import torch
+    st = np.ascontiguousarray(canonical_strides(model, n_blocks)[:3] * 2, dtype=np.int64)
     words = model.H * model.B * model.D * 2 // 8
-    v = mem.view(torch.int64).view(2 * model.L, n_blocks, words)
     out = torch.empty(2 * model.L, n_blocks, dtype=torch.int64, device=mem.device)
-    step = max(1, (1 << 28) // (n_blocks * words))  # planes per reduction call
-    for p in range(0, 2 * model.L, step):
-        out[p:p + step] = v[p:p + step].sum(dim=-1)
+    rc = _load().kvmw_block_hashes(mem.data_ptr(), st.ctypes.data, model.L, n_blocks, words,
+                                   out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("kvmw_block_hashes failed with %d" % rc)
     return out
+
+
+def block_hash_host(block_u16):
+    """The same hash of one block given as a uint16 array (numpy; for checking the kernel)."""
+    w = np.ascontiguousarray(block_u16).reshape(-1).view(np.uint64)
+    with np.errstate(over="ignore"):
+        z = w + (np.arange(1, len(w) + 1, dtype=np.uint64) * np.uint64(MIX64_GOLD))
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+        return int(z.sum(dtype=np.uint64))

@@ -97,6 +97,111 @@ extern "C" int kvmw_fill_pool(void* base_dev, const int64_t* strides_bytes, int 
   return 0;
 }
 
+// Regenerates chosen blocks of one plane into a dense buffer out[i][head][slot][dim]
+// (block i = generator content of block id ids[i]): what a pool block must hold if
+// it was filled by kvmw_fill_pool, without touching the pool.  Test support: lets a
+// check compare every block of a 100+ GiB pool against the generator on the device.
+struct GenArgs {
+  char* out;
+  const int32_t* ids;
+  int32_t H, B, D;
+  int32_t bf16;
+  uint32_t seed, stream, plane;
+};
+
+// grid: x = 8-element vectors of one block / 256, y = index into ids
+__global__ __launch_bounds__(256) void gen_blocks_kernel(const GenArgs a) {
+  const uint32_t dv = a.D / 8;
+  const uint32_t n_vec = (uint32_t)a.H * a.B * dv;
+  const uint32_t vec = blockIdx.x * 256u + threadIdx.x;
+  if (vec >= n_vec) return;
+  const uint32_t b = (uint32_t)a.ids[blockIdx.y];
+  const uint32_t key = mix32(a.seed ^ mix32(a.stream * 0x9E3779B9u + a.plane + 1u));
+  const uint32_t kb = mix32(key + b * 0x85EBCA6Bu);
+  const uint32_t w0 = vec * 8u;
+  uint32_t out[4];
+  for (int i = 0; i < 4; ++i)
+    out[i] = (uint32_t)gen16(kb, w0 + 2 * i, a.bf16) | ((uint32_t)gen16(kb, w0 + 2 * i + 1, a.bf16) << 16);
+  char* p = a.out + ((uint64_t)blockIdx.y * n_vec + vec) * 16u;
+  *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+extern "C" int kvmw_gen_blocks(void* out_dev, const int32_t* ids_dev, int64_t n_ids, int H, int B, int D,
+                               int bf16, uint32_t seed, uint32_t stream_id, uint32_t plane,
+                               void* hip_stream) {
+  if (!out_dev || !ids_dev || D % 8 || n_ids <= 0) return -1;
+  GenArgs a;
+  a.H = H; a.B = B; a.D = D;
+  a.bf16 = bf16;
+  a.seed = seed;
+  a.stream = stream_id;
+  a.plane = plane;
+  const uint32_t vecs = (uint32_t)H * B * (D / 8);
+  for (int64_t i = 0; i < n_ids; i += 32768) {
+    const int64_t n = n_ids - i < 32768 ? n_ids - i : 32768;
+    a.out = (char*)out_dev + (uint64_t)i * vecs * 16u;
+    a.ids = ids_dev + i;
+    hipLaunchKernelGGL(gen_blocks_kernel, dim3((vecs + 255) / 256, (uint32_t)n), dim3(256), 0,
+                       (hipStream_t)hip_stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
+}
+
+// Position-sensitive 64-bit hash of every (plane, block) of a pool whose blocks are
+// dense runs of `words` 8-byte words per plane:
+//   hash = sum_i mix64(word_i + (i + 1) * 0x9E3779B97F4A7C15)   (mod 2^64)
+// with mix64 the public splitmix64 finaliser.  Moving, swapping or changing words
+// inside a block changes the hash (a plain sum of the words would not see a
+// permutation).  Test support: "this block was left untouched" for pools too large
+// to compare on the host.
+static __host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// grid: x = block - b0, y = plane; out[plane][block]
+__global__ __launch_bounds__(256) void block_hash_kernel(const char* base, int64_t stride_layer,
+                                                         int64_t stride_kv, int64_t stride_block,
+                                                         uint32_t words, int64_t b0, int64_t n_blocks,
+                                                         unsigned long long* out) {
+  const uint32_t plane = blockIdx.y;
+  const int64_t b = b0 + blockIdx.x;
+  const uint64_t* p = reinterpret_cast<const uint64_t*>(
+      base + (int64_t)(plane >> 1) * stride_layer + (int64_t)(plane & 1) * stride_kv +
+      b * stride_block);
+  uint64_t acc = 0;
+  for (uint32_t i = threadIdx.x; i < words; i += 256)
+    acc += mix64(p[i] + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull);
+  // workgroup sum through LDS (addition mod 2^64 is order-independent)
+  __shared__ unsigned long long part[256];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[(int64_t)plane * n_blocks + b] = part[0];
+}
+
+// Hashes blocks [0, n_blocks) of all 2*L planes into out_dev[2L][n_blocks] (uint64).
+// strides_bytes: layer, kv, block; words = 8-byte words of one block's run in a plane.
+extern "C" int kvmw_block_hashes(const void* base_dev, const int64_t* strides_bytes, int L,
+                                 int64_t n_blocks, int64_t words, void* out_dev, void* hip_stream) {
+  if (!base_dev || !strides_bytes || !out_dev || n_blocks <= 0 || words <= 0 || words > 0x7fffffff) return -1;
+  for (int64_t b = 0; b < n_blocks; b += 1 << 20) {
+    const int64_t n = n_blocks - b < (1 << 20) ? n_blocks - b : (1 << 20);
+    hipLaunchKernelGGL(block_hash_kernel, dim3((uint32_t)n, 2 * L), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const char*)base_dev, strides_bytes[0], strides_bytes[1], strides_bytes[2],
+                       (uint32_t)words, b, n_blocks, (unsigned long long*)out_dev);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
+}
+
 // Plain contiguous device-to-device copy of `bytes` (multiple of 16) with 16-byte
 // vectors, 4 KiB per workgroup: the reference the benchmark reports beside the
 // gather/scatter kernels, and a kernel of known size for scaling HBM counters.
@@ -118,7 +223,7 @@ extern "C" int kvmw_plain_copy(void* dst_dev, const void* src_dev, int64_t bytes
   if (!dst_dev || !src_dev || bytes <= 0 || bytes % 16) return -1;
   const uint64_t n_vec = (uint64_t)bytes / 16;
   const uint64_t grid = (n_vec + 255) / 256;
-  if (grid > 0x7fffffffull) return -1;
+  if (grid > 0xffffffffull / 256) return -1;  // a grid dimension holds at most 2^32 - 1 work-items
   hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)hip_stream,
                      (const char*)src_dev, (char*)dst_dev, n_vec);
   return (int)hipGetLastError();

@@ -8,7 +8,7 @@ from .binding import (KVM_BEST_FIT, KVM_BF16, KVM_CLASS_DEFER, KVM_CLASS_KV, KVM
                       KVM_FIRST_FIT, KVM_EHIP, KVM_EINVAL, KVM_ENOMEM, KVM_F16, KVM_OK, Batch, FreeList,
                       KvmError, Pool, kvm_block_bytes, kvm_bytes_per_token,
                       kvm_decode_workspace_bytes, kvm_divide_moves, kvm_layout, kvm_layout_canonical, kvm_migrate,
-                      kvm_pack, kvm_paged_decode, kvm_paged_decode_static, kvm_pool_span_bytes,
+                      kvm_pack, kvm_paged_decode, kvm_paged_decode_rows, kvm_paged_decode_static, kvm_pool_span_bytes,
                       KVM_STATIC_SCRATCH_BYTES, kvm_set_option,
                       kvm_staging_bytes, kvm_unpack, lib)
 

@@ -76,6 +76,9 @@ def lib():
         L.kvm_paged_decode.restype = ctypes.c_int
         L.kvm_paged_decode.argtypes = [P(kvm_pool), P(kvm_batch), VP, VP, ctypes.c_int,
                                        ctypes.c_float, VP, I64, VP]
+        L.kvm_paged_decode_rows.restype = ctypes.c_int
+        L.kvm_paged_decode_rows.argtypes = [P(kvm_pool), P(kvm_batch), VP, VP, VP, ctypes.c_int,
+                                            ctypes.c_float, VP, I64, VP]
         L.kvm_paged_decode_static.restype = ctypes.c_int
         L.kvm_paged_decode_static.argtypes = [P(kvm_pool), P(kvm_batch), VP, VP, ctypes.c_int,
                                               ctypes.c_float, VP]
@@ -214,6 +217,17 @@ def kvm_paged_decode(pool, reqs, q, out, out_is_f32=True, scale=0.0, workspace=N
     return _check(lib().kvm_paged_decode(ctypes.byref(pool.c), ctypes.byref(reqs.c), _devptr(q),
                                          _devptr(out), 1 if out_is_f32 else 0, scale,
                                          _devptr(workspace), workspace_bytes or 0, _stream(stream)))
+
+
+def kvm_paged_decode_rows(pool, reqs, rows, q, out, out_is_f32=True, scale=0.0, workspace=None,
+                          workspace_bytes=None, stream=None):
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    assert len(rows) == reqs.n_req
+    if workspace is not None and workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return _check(lib().kvm_paged_decode_rows(ctypes.byref(pool.c), ctypes.byref(reqs.c), rows.ctypes.data,
+                                              _devptr(q), _devptr(out), 1 if out_is_f32 else 0, scale,
+                                              _devptr(workspace), workspace_bytes or 0, _stream(stream)))
 
 
 KVM_STATIC_SCRATCH_BYTES = 32 << 20  # as in kvm.h

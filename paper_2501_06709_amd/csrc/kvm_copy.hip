@@ -398,6 +398,7 @@ struct StageArgs {
   int32_t H, B;
   uint32_t DV;
   uint32_t piece_tokens;  // tokens per 256-vector piece (FAST only)
+  uint32_t n_wg;          // workgroups of this launch that have work
   FastDiv dvdiv, bdiv, heads;  // division by DV, B, H
   uint32_t first_wg[kMaxReqPerLaunch];  // densely packed, unused entries UINT32_MAX
   StageReq req[kMaxReqPerLaunch];
@@ -405,7 +406,11 @@ struct StageArgs {
 
 template <bool PACK, int U, bool NT, bool FAST>
 __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
-  const uint32_t wg = blockIdx.x;
+  // the launch's workgroups are numbered row by row over a 2-D grid (one grid
+  // dimension cannot hold them: a dimension is limited to 2^32 - 1 work-items);
+  // the last row may be ragged
+  const uint32_t wg = blockIdx.y * gridDim.x + blockIdx.x;
+  if (wg >= a.n_wg) return;
   // owning request: largest r with first_wg[r] <= wg (unused entries never compare true)
   int r = 0;
 #pragma unroll
@@ -548,7 +553,9 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
       ++r;
     }
     if (n_wg == 0) continue;
-    const dim3 grid((uint32_t)n_wg), block(256);
+    a.n_wg = (uint32_t)n_wg;
+    const StageGrid sg = stage_grid(n_wg);
+    const dim3 grid(sg.x, sg.y), block(256);
 #define KVM_STAGE2(UU, NT)                                                                       \
   do {                                                                                           \
     if (fast) hipLaunchKernelGGL((stage_kernel<PACK, UU, NT, true>), grid, block, 0, stream, a); \

@@ -45,8 +45,8 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no token seen yet"
 struct DecReq {
   int32_t bt;   // first table entry of the request
   int32_t k;    // context length
-  int32_t row;  // request index into q / out / workspace
-  int32_t pad;
+  int32_t row;  // row of q and out that belongs to the request
+  int32_t slot; // request index within the batch: its workspace entries
 };
 
 struct DecArgs {
@@ -140,7 +140,7 @@ __device__ __forceinline__ uint16_t narrow(float f) {
   return __builtin_bit_cast(uint16_t, (_Float16)f);
 }
 
-// Workspace entry of one (request row, layer, query head, split): D unnormalised
+// Workspace entry of one (request slot, layer, query head, split): D unnormalised
 // accumulator values, then the running max (exp2 domain) and the running sum.
 __device__ __forceinline__ float* ws_entry(float* ws, const DecArgs& a, int row, int l, int hq,
                                            int split, int D) {
@@ -200,7 +200,7 @@ __device__ __forceinline__ void reduce_states(const DecArgs& a, const DecReq& rq
       else
         reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
     } else {
-      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
+      float* e = ws_entry(a.ws, a, rq.slot, l, hq, split, D);
       e[d] = acc;
       if (d == 0) {
         e[D] = mx;
@@ -793,7 +793,7 @@ __global__ __launch_bounds__(256) void decode_shared_kernel(const DecArgs a) {
       else
         reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
     } else {
-      float* e = ws_entry(a.ws, a, rq.row, l, hq, split, D);
+      float* e = ws_entry(a.ws, a, rq.slot, l, hq, split, D);
       e[d] = acc;
       if (d == 0) {
         e[D] = mx;
@@ -814,10 +814,10 @@ __global__ __launch_bounds__(D) void merge_kernel(const DecArgs a) {
   const int n_eff = (nb + per - 1) / per;  // splits that saw at least one block
   const int d = threadIdx.x;
   float mx = kNegBig;
-  for (int s = 0; s < n_eff; ++s) mx = fmaxf(mx, ws_entry(a.ws, a, rq.row, l, hq, s, D)[D]);
+  for (int s = 0; s < n_eff; ++s) mx = fmaxf(mx, ws_entry(a.ws, a, rq.slot, l, hq, s, D)[D]);
   float acc = 0.f, den = 0.f;
   for (int s = 0; s < n_eff; ++s) {
-    const float* e = ws_entry(a.ws, a, rq.row, l, hq, s, D);
+    const float* e = ws_entry(a.ws, a, rq.slot, l, hq, s, D);
     const float wgt = __builtin_amdgcn_exp2f(e[D] - mx);
     acc = fmaf(e[d], wgt, acc);
     den = fmaf(e[D + 1], wgt, den);
@@ -1009,9 +1009,9 @@ static int static_scratch_ptr(void** out) {
 // Body of kvm_paged_decode and kvm_paged_decode_static.  With `static_scratch`
 // the context-split workspace is the library's own file-scope device array and
 // nothing is allocated; a plan whose workspace would not fit it is an error.
-static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
-                       int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
-                       bool static_scratch, void* hip_stream) {
+static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const int32_t* rows, const void* q_dev,
+                       void* out_dev, int out_is_f32, float scale, void* workspace_dev,
+                       int64_t workspace_bytes, bool static_scratch, void* hip_stream) {
   clear_error();
   BatchView v;
   int rc = validate_side(static_scratch ? "kvm_paged_decode_static" : "kvm_paged_decode", pool, reqs,
@@ -1020,6 +1020,18 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const void* 
   for (int r = 0; r < v.n_req; ++r)
     if (v.start[r] != 0) return fail(KVM_EINVAL, "kvm_paged_decode: reqs->start must be NULL or zero");
   if (v.n_req == 0 || v.total_blocks == 0) return KVM_OK;
+  if (rows) {
+    // rows of requests that produce output must be non-negative and distinct
+    std::vector<int32_t> used;
+    for (int r = 0; r < v.n_req; ++r)
+      if (v.k[r] > 0) {
+        if (rows[r] < 0) return fail(KVM_EINVAL, "kvm_paged_decode_rows: negative row");
+        used.push_back(rows[r]);
+      }
+    std::sort(used.begin(), used.end());
+    if (std::adjacent_find(used.begin(), used.end()) != used.end())
+      return fail(KVM_EINVAL, "kvm_paged_decode_rows: two requests share an output row");
+  }
   if (!q_dev || !out_dev) return fail(KVM_EINVAL, "kvm_paged_decode: q_dev or out_dev is NULL");
   if ((uintptr_t)q_dev % 16 || (uintptr_t)out_dev % 4)
     return fail(KVM_EINVAL, "kvm_paged_decode: q_dev must be 16-byte and out_dev 4-byte aligned");
@@ -1101,7 +1113,8 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const void* 
       const int r = order[r0 + i];
       a.req[i].bt = v.bt_off[r];
       a.req[i].k = v.k[r];
-      a.req[i].row = r;
+      a.req[i].row = rows ? rows[r] : r;
+      a.req[i].slot = r;
     }
     hipError_t e;
     const hipStream_t st = (hipStream_t)hip_stream;
@@ -1139,14 +1152,21 @@ int64_t kvm_decode_workspace_bytes(const kvm_layout* layout, const kvm_batch* re
 int kvm_paged_decode(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
                      int out_is_f32, float scale, void* workspace_dev, int64_t workspace_bytes,
                      void* hip_stream) {
-  return decode_impl(pool, reqs, q_dev, out_dev, out_is_f32, scale, workspace_dev, workspace_bytes,
+  return decode_impl(pool, reqs, nullptr, q_dev, out_dev, out_is_f32, scale, workspace_dev, workspace_bytes,
+                     /*static_scratch=*/false, hip_stream);
+}
+
+int kvm_paged_decode_rows(const kvm_pool* pool, const kvm_batch* reqs, const int32_t* rows,
+                          const void* q_dev, void* out_dev, int out_is_f32, float scale,
+                          void* workspace_dev, int64_t workspace_bytes, void* hip_stream) {
+  return decode_impl(pool, reqs, rows, q_dev, out_dev, out_is_f32, scale, workspace_dev, workspace_bytes,
                      /*static_scratch=*/false, hip_stream);
 }
 
 int kvm_paged_decode_static(const kvm_pool* pool, const kvm_batch* reqs, const void* q_dev, void* out_dev,
                             int out_is_f32, float scale, void* hip_stream) {
-  return decode_impl(pool, reqs, q_dev, out_dev, out_is_f32, scale, nullptr, 0, /*static_scratch=*/true,
-                     hip_stream);
+  return decode_impl(pool, reqs, nullptr, q_dev, out_dev, out_is_f32, scale, nullptr, 0,
+                     /*static_scratch=*/true, hip_stream);
 }
 
 }  // extern "C"

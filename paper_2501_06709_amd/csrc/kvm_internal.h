@@ -38,6 +38,22 @@ struct BatchView {
 int validate_side(const char* what, const kvm_pool* pool, const kvm_batch* batch, bool writing,
                   BatchView* out);
 
+// Grid of a launch whose n_wg 256-lane workgroups are numbered linearly (the
+// staging-order kernels): HIP holds each grid dimension in work-items as a 32-bit
+// value, so one dimension carries at most (2^32 - 1) / 256 workgroups (64 GiB of
+// staging at 4 KiB per workgroup).  Rows of 65536 workgroups, as many rows as
+// needed: x * y >= n_wg, x * 256 < 2^32, y <= 65535 for every n_wg < 2^31.
+struct StageGrid {
+  uint32_t x, y;
+};
+constexpr int64_t kStageGridRow = 65536;
+inline StageGrid stage_grid(int64_t n_wg) {
+  StageGrid g;
+  g.x = (uint32_t)(n_wg < kStageGridRow ? n_wg : kStageGridRow);
+  g.y = (uint32_t)ceil_div(n_wg, kStageGridRow);
+  return g;
+}
+
 struct Options {
   int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints

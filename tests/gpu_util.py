@@ -98,3 +98,55 @@ def oracle_migrate(orc, src, dst):
     orc.migrate(src.host, src.st, exp, dst.st, m.L, m.H, m.D, m.B, src.off, src.blk, dst.off,
                 dst.blk, src.k, start=src.start)
     return exp
+
+
+# ---- checks for pools too large for the host ----------------------------------
+# The pools are filled by the counter-based generator, whose device kernel and numpy
+# form agree bit for bit (tested on whole small pools).  What a block must hold after
+# a migration then follows from the definition at block granularity: destination
+# block bt_dst[j] of a request holds what the generator gives for its source block
+# bt_src[j].  That is compared for EVERY written block on the device; blocks that are
+# only partly written, and samples of the others, go to the host and through the
+# CPU oracle.
+
+def planes_view(mem, m, n_blocks):
+    """A dense canonical pool as int16 [2L][n_blocks][H*B*D]."""
+    return mem.view(torch.int16).view(2 * m.L, n_blocks, m.H * m.B * m.D)
+
+
+def assert_blocks_equal_generator(mem, m, n_blocks, ids, gen_ids, seed, stream, what, chunk_bytes=1 << 30):
+    """Every block ids[i] of the pool, in every plane, holds the generator's content
+    of block gen_ids[i] of `stream` (all on the device, in chunks)."""
+    from kvm_workload import device as wl_device
+    ids = np.asarray(ids, dtype=np.int64)
+    gen_ids = np.asarray(gen_ids, dtype=np.int32)
+    assert len(ids) == len(gen_ids)
+    if len(ids) == 0:
+        return
+    pv = planes_view(mem, m, n_blocks)
+    run = m.H * m.B * m.D
+    per = max(1, chunk_bytes // (run * 2))
+    exp = torch.empty(min(per, len(ids)) * run, dtype=torch.int16, device=mem.device)
+    for c in range(0, len(ids), per):
+        idx = torch.from_numpy(ids[c:c + per]).to(mem.device)
+        gid = torch.from_numpy(np.ascontiguousarray(gen_ids[c:c + per])).to(mem.device)
+        n = len(idx)
+        for p in range(2 * m.L):
+            wl_device.gen_blocks(exp, gid, m, seed, stream, p)
+            got = pv[p].index_select(0, idx)
+            if not torch.equal(got, exp[:n * run].view(n, run)):
+                bad = (got != exp[:n * run].view(n, run)).any(dim=1).nonzero().flatten()[:5].cpu().numpy()
+                raise AssertionError("%s: plane %d, blocks %s differ from the generator's blocks %s"
+                                     % (what, p, ids[c:c + per][bad], gen_ids[c:c + per][bad]))
+
+
+def full_and_partial(off, blk, k, B):
+    """Splits the blocks that hold tokens [0,k[r]) into completely written ones
+    (positions into blk) and, per request, the partly written last one."""
+    full, partial = [], []
+    for r in range(len(k)):
+        nfull = int(k[r]) // B
+        full.append(np.arange(off[r], off[r] + nfull))
+        if int(k[r]) % B:
+            partial.append((r, nfull, int(k[r]) % B))
+    return (np.concatenate(full) if full else np.zeros(0, np.int64)), partial

@@ -213,3 +213,45 @@ def test_fallback_kernel_for_other_shapes(oracle, m):
     assert np.abs(got[keep] - ref[keep]).max() < TOL
     got16 = wl.bits16_to_f64(gpu_decode(side, q, out_f32=False).view(np.uint16), m.dtype)
     assert np.abs(got16[keep] - ref[keep]).max() < 0.05
+
+
+def test_decode_rows_place_queries_and_outputs(oracle):
+    """kvm_paged_decode_rows: request r reads q row rows[r] and writes out row rows[r];
+    other rows of the output stay as they were; same bits as the identity call."""
+    m = wl.Model("gqa4", 2, 2, 8, 128, 16, "bf16")
+    lens = [100, 0, 333, 17]
+    src, _ = make_pair(m, 64, 8, [max(x, 1) for x in lens], [0] * 4, seed=31, finite=True)
+    side = Side(m, 64, src.host, src.tables, lens)
+    rows = np.array([5, 2, 0, 9], np.int32)            # row 2 belongs to the k = 0 request
+    q_small = wl.gen_q(31, m, 4)
+    q_big = np.zeros((12,) + q_small.shape[1:], np.uint16)
+    q_big[rows] = q_small
+    ref = gpu_decode(side, q_small)                    # identity rows
+    out = torch.full(q_big.shape, 7.0, dtype=torch.float32, device=DEV)
+    kvm.kvm_paged_decode_rows(side.pool, side.batch, rows, to_dev(q_big), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for r in (0, 2, 3):
+        assert np.array_equal(got[rows[r]], ref[r])
+    untouched = [i for i in range(12) if i not in (5, 0, 9)]
+    assert (got[untouched] == 7.0).all()
+    exp = oracle_decode(oracle, side, q_small)
+    assert np.abs(got[rows[[0, 2, 3]]] - exp[[0, 2, 3]]).max() < TOL
+    # long contexts: the split workspace is indexed by position in the batch, not by row
+    lens = [2500, 1800]
+    src, _ = make_pair(m, 300, 8, lens, [0] * 2, seed=32, finite=True)
+    side = Side(m, 300, src.host, src.tables, lens)
+    q_small = wl.gen_q(32, m, 2)
+    ref = gpu_decode(side, q_small)
+    rows = np.array([40, 3], np.int32)
+    q_big = np.zeros((41,) + q_small.shape[1:], np.uint16)
+    q_big[rows] = q_small
+    nws = kvm.kvm_decode_workspace_bytes(side.layout, side.batch)
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device=DEV)
+    out = torch.full(q_big.shape, 7.0, dtype=torch.float32, device=DEV)
+    kvm.kvm_paged_decode_rows(side.pool, side.batch, rows, to_dev(q_big), out, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy()[rows], ref)
+    with pytest.raises(kvm.KvmError):
+        kvm.kvm_paged_decode_rows(side.pool, side.batch, [3, 3], to_dev(q_big), out)

@@ -4,11 +4,13 @@ orders run back to back on one stream with a decode check after each.
 Shrunken case (three layouts with 2 layers, short requests): the whole arena is
 compared bit for bit with the CPU oracle carrying out the same orders, tables
 included, and every order's decode output is compared with the fp64 oracle.
-Full-size case (243 GiB arena, 512 requests, 200 orders): decode over the
-destination equals decode over the source bit for bit for every order, sampled
-decode rows match the oracle, every live request's blocks hold the generator's
-bytes of the blocks it started in, blocks never handed out are unchanged, and the
-free lists equal the complement of the live tables.
+Full-size case (243 GiB arena, 512 requests, 200 orders, staged 16 per flush as the
+benchmark runs them): every order's decode output equals decode over the source
+bit for bit and a sampled row of it matches the fp64 oracle; at the end EVERY block
+of every live request holds the generator's bytes of the block it started in
+(compared on the device, partly filled last blocks through the CPU oracle on the
+host), position-sensitive hashes show that blocks never handed out are unchanged,
+and the free lists equal the complement of the live tables.
 """
 import numpy as np
 import pytest
@@ -20,7 +22,7 @@ from kvm_workload import device as wl_device
 from kvm_workload import mixed
 from paper_2501_06709_amd.migrator import DevicePool, Migrator
 
-from gpu_util import DEV
+from gpu_util import DEV, assert_blocks_equal_generator, planes_view
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -74,7 +76,7 @@ def test_mixed_pool_shrunken_matches_oracle_everywhere(oracle):
         # oracle
         exp_ids = o_free[rq.model][1 - rq.half].alloc(-(-k // m.B))
         try:
-            ids = mig.move(rq.table, rq.length, src, dst, k, decode=(q_dev, out, None, 0))
+            ids = mig.move(rq.table, rq.length, src, dst, k, decode=(q_dev, out, 0))
         except kvm.KvmError as e:
             assert e.status == kvm.KVM_ENOMEM and exp_ids is None
             skipped += 1
@@ -130,29 +132,37 @@ def test_staged_orders_share_one_upload(oracle):
         return out
 
     mig = Migrator(DEV, max(len(rq.table) for rq in sc.requests), depth=4, max_staged=5)
+    # per model: query and output rows, one per order (row = order index)
+    n_ord = len(sc.orders)
+    q_all = [np.zeros((n_ord, m.L, m.Hq, m.D), np.uint16) for m in sc.models]
+    for oi, (ri, u) in enumerate(sc.orders):
+        mi = sc.requests[ri].model
+        q_all[mi][oi] = wl.gen_q(sc.seed + oi, sc.models[mi], 1)[0]
+    q_dev = [torch.from_numpy(q.view(np.int16)).to(DEV) for q in q_all]
+    out_dev = [torch.full(q.shape, 7.0, dtype=torch.float32, device=DEV) for q in q_all]
     checks = []
     moved = 0
     for oi, (ri, u) in enumerate(sc.orders):
         rq = sc.requests[ri]
         m = sc.models[rq.model]
         k = order_k(rq, u)
-        q = wl.gen_q(sc.seed + oi, m, 1)
-        q_dev = torch.from_numpy(q.view(np.int16)).to(DEV)
-        out = torch.zeros(q.shape, dtype=torch.float32, device=DEV)
         try:
             ids = mig.stage(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half], k,
-                            decode=(q_dev, out, None, 0))
+                            decode=(q_dev[rq.model], out_dev[rq.model], oi))
         except kvm.KvmError as e:
             assert e.status == kvm.KVM_ENOMEM
             continue
         if k > 0:
-            checks.append((oi, rq, k, q, q_dev, out, logical(rq, k)))   # content now: origin shrinks later
+            checks.append((oi, rq, k, q_all[rq.model][oi:oi + 1], None, out_dev[rq.model][oi:oi + 1],
+                           logical(rq, k)))   # content now: origin shrinks later
         rq.table, rq.length, rq.half = ids, k, 1 - rq.half
         rq.origin = rq.origin[:len(ids)]
         moved += 1
     mig.drain()
     torch.cuda.synchronize()
     assert moved >= 60
+    # orders were really grouped: fewer library calls than two per order
+    assert mig.launches < 2 * moved * 0.8, (mig.launches, moved)
     for oi, rq, k, q, _, out, kv in checks:                   # kv: [2L][H][k][D]
         m = sc.models[rq.model]
         nb = -(-k // m.B)
@@ -183,99 +193,131 @@ def test_staged_orders_share_one_upload(oracle):
             assert pools[mi][h].free.available() == sc.half_blocks[mi] - live
 
 
-def region_checksums(arena, sc):
+def region_hashes(arena, sc):
     out = {}
     for mi, m in enumerate(sc.models):
         n = sc.half_blocks[mi]
         for h in range(2):
             off = sc.half_offset[mi][h]
-            out[(mi, h)] = wl_device.plane_block_checksums(arena[off:off + n * m.block_bytes], m, n)
+            out[(mi, h)] = wl_device.plane_block_hashes(arena[off:off + n * m.block_bytes], m, n)
     return out
 
 
 def test_mixed_pool_full_size(oracle):
     sc = mixed.make()
+    torch.cuda.empty_cache()            # memory an earlier test's tensors left in torch's cache
     free_b, _ = torch.cuda.mem_get_info()
     if sc.arena_bytes + (12 << 30) > free_b:
         pytest.skip("needs %.0f GiB of HBM" % (sc.arena_bytes / 2**30))
     arena, pools = build_device(sc)
-    before = region_checksums(arena, sc)
+
+    def region(mi, h):
+        off = sc.half_offset[mi][h]
+        return arena[off:off + sc.half_blocks[mi] * sc.models[mi].block_bytes]
+
+    before = region_hashes(arena, sc)
     handed_out = {key: np.zeros(sc.half_blocks[key[0]], bool) for key in before}
     rng = np.random.default_rng(3)
     max_nb = max(len(rq.table) for rq in sc.requests)
-    mig = Migrator(DEV, max_nb)
-    moved = skipped = 0
-    worst = 0.0
+    mig = Migrator(DEV, max_nb)                       # 16 orders per flush, as the benchmark
+    # one query / output row per order, per model
+    n_ord = len(sc.orders)
+    q_all = [np.zeros((n_ord, m.L, m.Hq, m.D), np.uint16) for m in sc.models]
+    for oi, (ri, u) in enumerate(sc.orders):
+        mi = sc.requests[ri].model
+        q_all[mi][oi] = wl.gen_q(sc.seed + oi, sc.models[mi], 1)[0]
+    q_dev = [torch.from_numpy(q.view(np.int16)).to(DEV) for q in q_all]
+    out_dst = [torch.full(q.shape, 7.0, dtype=torch.float32, device=DEV) for q in q_all]
+    out_src = [torch.full(q.shape, 9.0, dtype=torch.float32, device=DEV) for q in q_all]
+    done = []
     for oi, (ri, u) in enumerate(sc.orders):
         rq = sc.requests[ri]
         m = sc.models[rq.model]
         k = order_k(rq, u)
         src, dst = pools[rq.model][rq.half], pools[rq.model][1 - rq.half]
-        q = wl.gen_q(sc.seed + oi, m, 1)
-        q_dev = torch.from_numpy(q.view(np.int16)).to(DEV)
-        out = torch.zeros(q.shape, dtype=torch.float32, device=DEV)
-        out_src = torch.zeros_like(out)
-        # decode over the first k tokens of the source, before anything moves
+        old_table = np.asarray(rq.table, np.int32)
+        ids = mig.stage(rq.table, rq.length, src, dst, k, decode=(q_dev[rq.model], out_dst[rq.model], oi))
+        # decode over the first k tokens of the source, row oi.  After stage(): had the
+        # request been moved by an order that is still staged, stage() has enqueued it.
         if k > 0:
-            tab_dev = torch.from_numpy(np.asarray(rq.table, np.int32)).to(DEV)
-            sb = kvm.Batch([0, len(rq.table)], rq.table, [k], tab_dev)
-            kvm.kvm_paged_decode(src.pool, sb, q_dev, out_src)
-        try:
-            ids = mig.move(rq.table, rq.length, src, dst, k, decode=(q_dev, out, None, 0))
-        except kvm.KvmError as e:
-            assert e.status == kvm.KVM_ENOMEM
-            skipped += 1
-            continue
+            tab_dev = torch.from_numpy(old_table).to(DEV)
+            sb = kvm.Batch([0, len(old_table)], old_table, [k], tab_dev)
+            kvm.kvm_paged_decode_rows(src.pool, sb, [oi], q_dev[rq.model], out_src[rq.model])
         handed_out[(rq.model, 1 - rq.half)][ids] = True
-        torch.cuda.synchronize()
-        assert torch.equal(out, out_src), "order %d: decode over destination != decode over source" % oi
-        if k > 0:
-            # one sampled (layer, query head) row against the fp64 oracle on regenerated K/V
-            l, hq = int(rng.integers(m.L)), int(rng.integers(m.Hq))
-            g = hq // (m.Hq // m.H)
-            nb = -(-k // m.B)
-            wsel = (g * m.B * m.D + np.arange(m.B * m.D)).astype(np.uint32)
-            kv = np.zeros((2, nb, m.B * m.D), dtype=np.uint16)
-            for j in range(nb):
-                oh, ob = rq.origin[j]
-                for c in range(2):
-                    kv[c, j] = wl.gen_values(sc.seed, sc.stream(rq.model, oh), 2 * l + c, ob, wsel, m.dtype)
-            st1 = oracle.canonical_strides(1, 1, m.D, m.B, nb)
-            ref = oracle.paged_decode(kv.reshape(-1), st1, 1, 1, 1, m.D, m.B, m.dtype, [0, nb],
-                                      np.arange(nb), [k], q[0, l, hq].reshape(1, 1, 1, m.D))
-            err = float(np.abs(out[0, l, hq].cpu().numpy().astype(np.float64) - ref[0, 0, 0]).max())
-            worst = max(worst, err)
-            assert err < TOL, (oi, err)
+        done.append((oi, rq, k, list(rq.origin[:len(ids)])))
         rq.table, rq.length, rq.half = ids, k, 1 - rq.half
         rq.origin = rq.origin[:len(ids)]
-        moved += 1
     mig.drain()
     torch.cuda.synchronize()
-    assert moved >= 150, (moved, skipped)
+    assert len(done) == len(sc.orders) == 200         # no order was refused for lack of blocks
+    assert mig.launches < 2 * len(done) * 0.8         # the orders of a flush were grouped
+    worst = 0.0
+    for oi, rq, k, origin in done:
+        if k == 0:
+            continue
+        m = sc.models[rq.model]
+        assert torch.equal(out_dst[rq.model][oi], out_src[rq.model][oi]), \
+            "order %d: decode over destination != decode over source" % oi
+        # one sampled (layer, query head) row against the fp64 oracle on regenerated K/V
+        l, hq = int(rng.integers(m.L)), int(rng.integers(m.Hq))
+        g = hq // (m.Hq // m.H)
+        nb = -(-k // m.B)
+        wsel = (g * m.B * m.D + np.arange(m.B * m.D)).astype(np.uint32)
+        kv = np.zeros((2, nb, m.B * m.D), dtype=np.uint16)
+        for j in range(nb):
+            oh, ob = origin[j]
+            for c in range(2):
+                kv[c, j] = wl.gen_values(sc.seed, sc.stream(rq.model, oh), 2 * l + c, ob, wsel, m.dtype)
+        st1 = oracle.canonical_strides(1, 1, m.D, m.B, nb)
+        ref = oracle.paged_decode(kv.reshape(-1), st1, 1, 1, 1, m.D, m.B, m.dtype, [0, nb],
+                                  np.arange(nb), [k], q_all[rq.model][oi, l, hq].reshape(1, 1, 1, m.D))
+        err = float(np.abs(out_dst[rq.model][oi, l, hq].cpu().numpy().astype(np.float64) - ref[0, 0, 0]).max())
+        worst = max(worst, err)
+        assert err < TOL, (oi, err)
     # blocks never handed out are unchanged; free lists = complement of the live tables
-    after = region_checksums(arena, sc)
+    after = region_hashes(arena, sc)
     for key in before:
         changed = (after[key] != before[key]).any(dim=0).cpu().numpy()
         assert not (changed & ~handed_out[key]).any(), "a block that was never allocated changed"
         mi, h = key
         live = int(mixed.occupancy(sc, mi, h).sum())
         assert pools[mi][h].free.available() == sc.half_blocks[mi] - live
-    # content identity: sampled live blocks hold the bytes of the blocks they started in
-    movers = [rq for rq in sc.requests if rq.length > 0 and rq.origin and
-              (rq.half, int(rq.table[0])) != rq.origin[0]]
-    for rq in [movers[i] for i in rng.choice(len(movers), size=12)]:
+    # content identity, complete: every block of every live request holds the bytes of
+    # the block it started in (full blocks on the device, partly filled last blocks
+    # through the oracle on the host)
+    n_checked = 0
+    for mi, m in enumerate(sc.models):
+        n = sc.half_blocks[mi]
+        for h in range(2):
+            for oh in range(2):
+                cur, org = [], []
+                for rq in sc.requests:
+                    if rq.model != mi or rq.half != h:
+                        continue
+                    for j in range(rq.length // m.B):
+                        if rq.origin[j][0] == oh:
+                            cur.append(int(rq.table[j]))
+                            org.append(rq.origin[j][1])
+                assert_blocks_equal_generator(region(mi, h), m, n, cur, org, sc.seed, sc.stream(mi, oh),
+                                              "model %d half %d (origin half %d)" % (mi, h, oh))
+                n_checked += len(cur)
+    for rq in sc.requests:
+        ns = rq.length % sc.models[rq.model].B
+        if ns == 0:
+            continue
         m = sc.models[rq.model]
-        n = sc.half_blocks[rq.model]
-        off = sc.half_offset[rq.model][rq.half]
-        run = m.H * m.B * m.D
-        planes = arena[off:off + n * m.block_bytes].view(torch.int16).view(2 * m.L, n, run)
-        nb = -(-rq.length // m.B)
-        for j in {0, nb - 1, int(rng.integers(nb))}:
-            p = int(rng.integers(2 * m.L))
-            ns = min(m.B, rq.length - j * m.B)
-            oh, ob = rq.origin[j]
-            exp = wl.gen_block(sc.seed, sc.stream(rq.model, oh), m, p, ob)
-            got = planes[p, int(rq.table[j])].cpu().numpy().view(np.uint16).reshape(m.H, m.B, m.D)
-            assert np.array_equal(got[:, :ns], exp[:, :ns])
-    print("mixed: %d orders moved, %d skipped for lack of blocks, worst sampled decode error %.2e"
-          % (moved, skipped, worst))
+        j = rq.length // m.B
+        oh, ob = rq.origin[j]
+        st1 = oracle.canonical_strides(m.L, m.H, m.D, m.B, 1)
+        mini_src = np.stack([wl.gen_block(sc.seed, sc.stream(rq.model, oh), m, p, ob) for p in range(2 * m.L)])
+        exp = np.zeros_like(mini_src).reshape(-1)
+        oracle.migrate(mini_src.reshape(-1), st1, exp, st1, m.L, m.H, m.D, m.B, [0, 1], [0], [0, 1], [0], [ns])
+        got = planes_view(region(rq.model, rq.half), m, sc.half_blocks[rq.model])[:, int(rq.table[j])]
+        got = got.cpu().numpy().view(np.uint16).reshape(2 * m.L, m.H, m.B, m.D)
+        assert np.array_equal(got[:, :, :ns], exp.reshape(got.shape)[:, :, :ns]), "last block of a request"
+        n_checked += 1
+    assert n_checked == sum(len(rq.table) for rq in sc.requests if rq.length > 0)
+    print("mixed: %d orders in %d library calls, %d live blocks checked, worst sampled decode error %.2e"
+          % (len(done), mig.launches, n_checked, worst))
+    del arena, pools, mig
+    torch.cuda.empty_cache()

@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--order", type=int, default=None)
     ap.add_argument("--split-target", type=int, default=None)
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--no-reference-legs", action="store_true",
+                    help="skip the table-free reference access patterns (they overwrite the destination pool)")
     ap.add_argument("--q-heads", type=int, default=None,
                     help="query heads of the decode leg (a multiple of the KV heads); e.g. 64 on "
                          "llama3_8b_gqa gives the 70B-class group of eight over the same KV")
@@ -214,9 +216,12 @@ def bench_mixed(a, log):
         try:
             # staged: up to 16 orders per flush; a flush is one table upload and, per
             # (model, direction), one fused-migrate and one decode launch over its orders
+            # rows: any n_stage consecutive orders (a flush never holds more) get distinct ones
             ids = mig.stage(rq.table, rq.length, pools[rq.model][rq.half], pools[rq.model][1 - rq.half],
-                            k, decode=(qs[rq.model], outs[rq.model], len(mig.staged) % n_stage))
-        except kvm.KvmError:
+                            k, decode=(qs[rq.model], outs[rq.model], (moved + skipped) % n_stage))
+        except kvm.KvmError as e:
+            if e.status != kvm.KVM_ENOMEM:
+                raise
             skipped += 1
             continue
         rq.table, rq.length, rq.half = ids, k, 1 - rq.half
@@ -231,6 +236,7 @@ def bench_mixed(a, log):
     log("%d orders moved (%d skipped) in %.1f ms, %d library calls" % (moved, skipped, dt * 1e3,
                                                                       mig.launches - launches0))
     gbs = nbytes / dt / 1e9
+    hbm_gbs = 1.5 * nbytes / dt / 1e9      # + the decode's read of every moved byte
     copy_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in mig.copy_marks)
     copy_bytes = sum(b for _, _, b in mig.copy_marks)
     copy_gbs = copy_bytes / (copy_ms * 1e-3) / 1e9
@@ -246,12 +252,308 @@ def bench_mixed(a, log):
                    "value_is": "2 x moved bytes per second of wall time over the whole order stream, "
                                "decode over each destination and host work included"},
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "sustained_hbm": {"GB/s": round(hbm_gbs, 1), "frac_of_hbm_peak": round(hbm_gbs / HBM_PEAK_GBS, 4),
+                          "is": "bytes read + written by the copies plus bytes read by the decodes, per "
+                                "second of wall time"},
         "orders_per_s": round(moved / dt, 1), "migrated_blocks_per_s": round(blocks / dt, 1),
         "roofline": {"kernel": "copy_kernel<migrate> (kvm_migrate), all launches of the stream",
                      "bound": "hbm", "achieved": round(copy_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(copy_gbs / HBM_PEAK_GBS, 4),
                      "launches": len(mig.copy_marks), "algorithmic_bytes": copy_bytes,
                      "traffic": None}}), flush=True)
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: the migration path here has no multi-GPU part "
+              "(--gpus %d refused)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    def log(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+
+    import kvm_workload as wl
+    import paper_2501_06709_amd as kvm
+    from kvm_workload import device as wl_device
+
+    kvm.lib()  # fails loudly if the HIP library is not built
+    for name, val in (("copy.unroll", a.unroll), ("copy.nontemporal", a.nontemporal),
+                      ("copy.order", a.order), ("decode.split_target", a.split_target)):
+        if val is not None:
+            kvm.kvm_set_option(name, val)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if a.config == "mixed":
+        return bench_mixed(a, log)
+    w = wl.make(a.config)
+    m = w.model
+    payload = w.payload_bytes()
+    free_b, total_b = torch.cuda.mem_get_info()
+    log("HBM free %.1f GiB of %.1f GiB; workload %s payload %.2f GiB"
+        % (free_b / 2**30, total_b / 2**30, w.name, payload / 2**30))
+    # room beside the pools: staging for at least the largest request, tables, q, out
+    w = fit_pools(w, free_b, int(w.k.max()) * m.bytes_per_token + (2 << 30), log)
+    if a.q_heads is not None:   # only the decode leg sees the query heads
+        import dataclasses
+        w.model = m = dataclasses.replace(w.model, Hq=a.q_heads)
+        w.notes = list(w.notes) + ["query heads overridden to %d" % a.q_heads]
+    payload = w.payload_bytes()
+
+    lay_s = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_src)
+    lay_d = kvm.kvm_layout_canonical(m.L, m.H, m.Hq, m.D, m.B, m.dtype, w.n_blocks_dst)
+    src_mem = torch.empty(kvm.kvm_pool_span_bytes(lay_s, w.n_blocks_src), dtype=torch.uint8, device=dev)
+    dst_mem = torch.empty(kvm.kvm_pool_span_bytes(lay_d, w.n_blocks_dst), dtype=torch.uint8, device=dev)
+    t0 = time.perf_counter()
+    wl_device.fill_pool(src_mem, m, w.n_blocks_src, w.seed, wl.STREAM_SRC)
+    wl_device.fill_pool(dst_mem, m, w.n_blocks_dst, w.seed, wl.STREAM_DST)
+    torch.cuda.synchronize()
+    log("pools: src %d blocks (%.1f GiB), dst %d blocks (%.1f GiB), filled in %.2f s"
+        % (w.n_blocks_src, src_mem.numel() / 2**30, w.n_blocks_dst, dst_mem.numel() / 2**30,
+           time.perf_counter() - t0))
+    src_pool = kvm.Pool(src_mem, w.n_blocks_src, lay_s)
+    dst_pool = kvm.Pool(dst_mem, w.n_blocks_dst, lay_d)
+
+    # source side: tables of the migrated requests; free list = blocks no live request holds
+    s_off, s_blk = w.src_csr()
+    s_blk_dev = torch.from_numpy(s_blk).to(dev)
+    src_batch = kvm.Batch(s_off, s_blk, w.k, s_blk_dev)
+    src_occ = np.zeros(w.n_blocks_src, np.uint8)
+    src_occ[np.concatenate(w.src_tables)] = 1
+    src_fl = kvm.FreeList(w.n_blocks_src, src_occ)
+    dst_fl = kvm.FreeList(w.n_blocks_dst, w.dst_occupied)
+
+    nbk = w.n_dst_blocks()
+    n_dst = int(sum(nbk))
+    d_off = np.zeros(len(nbk) + 1, np.int32)
+    d_off[1:] = np.cumsum(nbk)
+    d_blk_pin = torch.empty(max(n_dst, 1), dtype=torch.int32, pin_memory=True)
+    d_blk_dev = torch.empty(max(n_dst, 1), dtype=torch.int32, device=dev)
+    # The staged path needs a staging buffer; when the whole batch's does not fit
+    # beside the pools it is run in groups of consecutive requests.
+    free_now, _ = torch.cuda.mem_get_info()
+    stage_budget = max(free_now - (4 << 30), 1 << 20)
+    groups, g0, acc = [], 0, 0
+    for r, kr in enumerate(w.k):
+        b = int(kr) * m.bytes_per_token
+        if b > stage_budget:
+            raise SystemExit("one request's staging (%d B) does not fit in HBM" % b)
+        if acc + b > stage_budget:
+            groups.append((g0, r))
+            g0, acc = r, 0
+        acc += b
+    groups.append((g0, len(w.k)))
+    stage_bytes = max(int(w.k[lo:hi].astype(np.int64).sum()) * m.bytes_per_token for lo, hi in groups)
+    staging = torch.empty(max(stage_bytes, 16), dtype=torch.uint8, device=dev)
+    if len(groups) > 1:
+        log("staged path runs in %d request groups (staging buffer %.1f GiB)"
+            % (len(groups), stage_bytes / 2**30))
+    q_host = wl.gen_q(w.seed, m, len(w.k))
+    q_dev = torch.from_numpy(q_host.view(np.int16)).to(dev)
+    out = torch.zeros(q_host.shape, dtype=torch.float32, device=dev)
+    probe = kvm.Batch(d_off, np.zeros(n_dst, np.int32), w.k, d_blk_dev)
+    ws_bytes = kvm.kvm_decode_workspace_bytes(lay_d, probe)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def sub_batch(off, blk, blk_dev, lo, hi):
+        """Requests [lo,hi) of a batch as a batch of their own (pointer arithmetic only)."""
+        o = off[lo:hi + 1] - off[lo]
+        return kvm.Batch(o, blk[off[lo]:off[hi]], w.k[lo:hi], blk_dev.data_ptr() + 4 * int(off[lo]))
+
+    src_groups = [sub_batch(s_off, s_blk, s_blk_dev, lo, hi) for lo, hi in groups]
+    names = ("pack", "unpack", "migrate", "decode")
+    stream = torch.cuda.current_stream()
+
+    def step(events):
+        # allocate destination blocks, rewrite and upload the block table
+        ids = dst_fl.alloc(n_dst)
+        d_blk_pin.numpy()[:n_dst] = ids
+        d_blk_dev.copy_(d_blk_pin, non_blocking=True)
+        dst_batch = kvm.Batch(d_off, ids, w.k, d_blk_dev)
+        marks = []
+
+        def timed(name, fn):
+            if events is None:
+                return fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            marks.append((name, e0, e1))
+
+        for (lo, hi), sg in zip(groups, src_groups):
+            dg = dst_batch if len(groups) == 1 else sub_batch(d_off, ids, d_blk_dev, lo, hi)
+            nbytes = int(w.k[lo:hi].astype(np.int64).sum()) * m.bytes_per_token
+            timed("pack", lambda: kvm.kvm_pack(src_pool, sg, staging, staging_bytes=nbytes))
+            timed("unpack", lambda: kvm.kvm_unpack(staging, dst_pool, dg, staging_bytes=nbytes))
+        timed("migrate", lambda: kvm.kvm_migrate(src_pool, src_batch, dst_pool, dst_batch))
+        done = torch.cuda.Event()
+        done.record(stream)
+        timed("decode", lambda: kvm.kvm_paged_decode(dst_pool, dst_batch, q_dev, out, workspace=ws,
+                                                     workspace_bytes=ws_bytes))
+        if events is not None:
+            events.append(marks)
+        # the source blocks may be released only once the copies have finished
+        done.synchronize()
+        src_fl.free(s_blk)
+        # bookkeeping so that the next step starts from the same state
+        src_fl.reserve(s_blk)
+        dst_fl.free(ids)
+        return ids
+
+    for _ in range(a.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        ids = step(events)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t0
+    ms_step = t_total * 1e3 / a.steps
+    kern_ms = {n: float(np.mean([sum(e0.elapsed_time(e1) for nm, e0, e1 in marks if nm == n)
+                                 for marks in events])) for n in names}
+    log("step %.3f ms; kernels (ms): %s" % (ms_step, {k: round(v, 4) for k, v in kern_ms.items()}))
+
+    # practical ceiling: a plain contiguous device-to-device copy of the same payload
+    # (one half of the staging buffer copied onto the other: no extra allocation)
+    nb16 = min(payload, stage_bytes // 2) // 16 * 16
+    half_a, half_b = staging[:nb16], staging[nb16:2 * nb16]
+    for _ in range(2):
+        wl_device.plain_copy(half_b, half_a, nb16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(5):
+        wl_device.plain_copy(half_b, half_a, nb16)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    memcpy_gbs = 2 * nb16 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    # end-state check on sampled blocks: destination equals source, source equals generator
+    verified = None
+    if not a.no_verify:
+        run = m.H * m.B * m.D
+        sp = src_mem.view(torch.int16).view(2 * m.L, w.n_blocks_src, run)
+        dp = dst_mem.view(torch.int16).view(2 * m.L, w.n_blocks_dst, run)
+        rng = np.random.default_rng(1)
+        bad = 0
+        for _ in range(16):
+            r = int(rng.integers(len(w.k)))
+            if nbk[r] == 0:
+                continue
+            j = int(rng.integers(nbk[r]))
+            p = int(rng.integers(2 * m.L))
+            ns = min(m.B, int(w.k[r]) - j * m.B)
+            sblk = int(s_blk[s_off[r] + j])
+            dblk = int(ids[d_off[r] + j])
+            s_h = sp[p, sblk].cpu().numpy().view(np.uint16).reshape(m.H, m.B, m.D)
+            d_h = dp[p, dblk].cpu().numpy().view(np.uint16).reshape(m.H, m.B, m.D)
+            gen_s = wl.gen_block(w.seed, wl.STREAM_SRC, m, p, sblk)
+            gen_d = wl.gen_block(w.seed, wl.STREAM_DST, m, p, dblk)
+            ok = (np.array_equal(s_h, gen_s) and np.array_equal(d_h[:, :ns], gen_s[:, :ns])
+                  and np.array_equal(d_h[:, ns:], gen_d[:, ns:]))
+            bad += 0 if ok else 1
+        verified = bad == 0
+        log("sampled end-state check: %s" % ("ok" if verified else "%d MISMATCHES" % bad))
+
+    # reference access patterns from arithmetic addresses (no tables): the ceilings the
+    # memory system gives a kernel of the copy kernels' shape, over the same pools
+    reference = None
+    if not a.no_reference_legs:
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        legs = [  # name, mode, run bytes, source random, destination random
+            ("read_stream", wl_device.REF_READ, 4096, False, False),
+            ("write_stream", wl_device.REF_WRITE, 4096, False, False),
+            ("read_random_4k", wl_device.REF_READ, 4096, True, False),
+            ("read_random_32k", wl_device.REF_READ, 32768, True, False),
+            ("write_random_32k", wl_device.REF_WRITE, 32768, False, True),
+            ("copy_stream", wl_device.REF_COPY, 32768, False, False),
+            ("copy_random_src_32k", wl_device.REF_COPY, 32768, True, False),
+            ("copy_random_dst_32k", wl_device.REF_COPY, 32768, False, True),
+            ("copy_random_both_32k", wl_device.REF_COPY, 32768, True, True),
+        ]
+        reference = {}
+        for name, mode, run, rs, rd in legs:
+            n_runs = payload // run
+            args = (mode, src_mem if mode != wl_device.REF_WRITE else None,
+                    dst_mem if mode != wl_device.REF_READ else None, run, n_runs, rs, rd, sink)
+            for _ in range(2):
+                wl_device.ref_stream(*args)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                wl_device.ref_stream(*args)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            moved = n_runs * run * (2 if mode == wl_device.REF_COPY else 1)
+            reference[name] = {"GB/s": round(moved * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1),
+                               "bytes": moved}
+        log("reference legs (GB/s): %s" % {k: v["GB/s"] for k, v in reference.items()})
+
+    value = 6 * payload / (ms_step * 1e-3) / 1e9
+    mig_gbs = 2 * payload / (kern_ms["migrate"] * 1e-3) / 1e9
+    result = {
+        "metric": "KV migrate GB/s (read+write)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name,
+            "shape": "L%d H%d Hq%d D%d B%d %s" % (m.L, m.H, m.Hq, m.D, m.B, m.dtype),
+            "pool_blocks": [w.n_blocks_src, w.n_blocks_dst],
+            "live_requests": len(w.lens),
+            "migrated_requests": len(w.k),
+            "migrated_tokens": int(w.k.sum()),
+            "migrated_blocks": n_dst,
+            "payload_bytes": payload,
+            "value_is": "bytes read+written by pack, unpack and fused migrate (6 x payload) per "
+                        "second of whole-step time; the step also allocates, uploads the table, "
+                        "runs paged decode over the destination and releases the source",
+            "notes": w.notes,
+        },
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "migrated_blocks_per_s": round(n_dst / (kern_ms["migrate"] * 1e-3), 1),
+        "kernels": {
+            "pack": {"ms": round(kern_ms["pack"], 4),
+                     "GB/s": round(2 * payload / kern_ms["pack"] / 1e6, 1),
+                     "frac_of_hbm_peak": round(2 * payload / kern_ms["pack"] / 1e6 / HBM_PEAK_GBS, 4)},
+            "unpack": {"ms": round(kern_ms["unpack"], 4),
+                       "GB/s": round(2 * payload / kern_ms["unpack"] / 1e6, 1),
+                       "frac_of_hbm_peak": round(2 * payload / kern_ms["unpack"] / 1e6 / HBM_PEAK_GBS, 4)},
+            "migrate": {"ms": round(kern_ms["migrate"], 4), "GB/s": round(mig_gbs, 1),
+                        "frac_of_hbm_peak": round(mig_gbs / HBM_PEAK_GBS, 4)},
+            "decode": {"ms": round(kern_ms["decode"], 4),
+                       "GB/s": round(payload / kern_ms["decode"] / 1e6, 1),
+                       "frac_of_hbm_peak": round(payload / kern_ms["decode"] / 1e6 / HBM_PEAK_GBS, 4)},
+            "plain_copy": {"GB/s": round(memcpy_gbs, 1), "bytes": nb16},
+        },
+        "reference": reference,
+        "verified": verified,
+        "roofline": {
+            "kernel": "copy_kernel<migrate> (kvm_migrate)",
+            "bound": "hbm",
+            "achieved": round(mig_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(mig_gbs / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+        },
+    }
+    if not a.no_cpu_baseline:
+        del staging
+        result["cpu_baseline"] = cpu_baseline(w, src_mem, m.bytes_per_token, a.cpu_sample, log)
+    print(json.dumps(result), flush=True)
 
 
 if __name__ == "__main__":

@@ -36,6 +36,10 @@ def _load():
         _lib.kvmw_block_hashes.restype = ctypes.c_int
         _lib.kvmw_block_hashes.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                                            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        _lib.kvmw_ref_stream.restype = ctypes.c_int
+        _lib.kvmw_ref_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_void_p]
         _lib.kvmw_plain_copy.restype = ctypes.c_int
         _lib.kvmw_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p]
@@ -49,6 +53,34 @@ def plain_copy(dst, src, nbytes):
                                  torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError("kvmw_plain_copy failed with %d" % rc)
+
+
+REF_COPY, REF_READ, REF_WRITE = 0, 1, 2
+
+
+def ref_stream(mode, src, dst, run_bytes, n_runs, src_random, dst_random, sink):
+    """One launch of the reference access-pattern kernel (see fill.hip): n_runs runs of
+    run_bytes each, read from `src` and / or written to `dst` (torch tensors spanning
+    the buffers), at consecutive run slots or at pseudo-randomly permuted slots over
+    the largest power-of-two number of slots the buffer holds."""
+    import torch
+
+    def bits(buf, random):
+        slots = buf.numel() * buf.element_size() // run_bytes
+        assert slots >= n_runs
+        if not random:
+            return 0
+        b = slots.bit_length() - 1            # 2^b <= slots
+        assert n_runs <= 1 << b
+        return b
+
+    rc = _load().kvmw_ref_stream(mode, src.data_ptr() if src is not None else None,
+                                 dst.data_ptr() if dst is not None else None, run_bytes, n_runs,
+                                 bits(src, src_random) if src is not None else 0,
+                                 bits(dst, dst_random) if dst is not None else 0,
+                                 sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("kvmw_ref_stream failed with %d" % rc)
 
 
 def fill_pool(mem, model, n_blocks, seed, stream_id, strides=None, b0=0, b1=None):

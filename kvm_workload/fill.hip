@@ -228,3 +228,81 @@ extern "C" int kvmw_plain_copy(void* dst_dev, const void* src_dev, int64_t bytes
                      (const char*)src_dev, (char*)dst_dev, n_vec);
   return (int)hipGetLastError();
 }
+
+
+// Reference access patterns for the benchmark (no tables, no requests): what the
+// memory system gives a kernel of the same shape as the library's copy kernels
+// (256 lanes, one 16-byte vector per lane, 4 KiB per workgroup, the same
+// cache-policy bits) when the addresses come from arithmetic alone.
+//   mode 0: copy   mode 1: read only   mode 2: write only
+// The buffer on each side is cut into runs of `run_vecs` vectors; workgroup w works
+// on chunk (w % chunks) of run (w / chunks); run r sits at run slot r of its side
+// (bits = 0: sequential) or at slot perm(r), a fixed pseudo-random permutation of
+// the side's first 2^bits slots (multiply by an odd constant, xor the upper half
+// into the lower, multiply again: each step is a bijection on `bits`-bit values).
+struct RefArgs {
+  const char* src;
+  char* dst;
+  uint32_t run_vecs, chunks;     // vectors per run, workgroups per run
+  uint64_t n_runs;
+  uint32_t src_bits, dst_bits;
+  int32_t mode;
+  uint32_t* sink;                // read-only mode: never written unless a loaded word equals the magic
+};
+
+__device__ inline uint64_t ref_perm(uint64_t r, uint32_t bits) {
+  if (bits == 0) return r;
+  const uint64_t mask = (1ull << bits) - 1;
+  r = (r * 0x9E3779B97F4A7C15ull) & mask;
+  r ^= r >> ((bits + 1) / 2);
+  r = (r * 0xBF58476D1CE4E5B9ull) & mask;
+  r ^= r >> ((bits + 1) / 2);
+  return r;
+}
+
+__global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
+  const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+  const uint64_t r = w / a.chunks;
+  if (r >= a.n_runs) return;
+  const uint32_t v = (uint32_t)(w - r * a.chunks) * 256u + threadIdx.x;
+  if (v >= a.run_vecs) return;
+  const uint64_t s_slot = ref_perm(r, a.src_bits), d_slot = ref_perm(r, a.dst_bits);
+  const kvmw_v4u* sp = reinterpret_cast<const kvmw_v4u*>(a.src) + s_slot * a.run_vecs + v;
+  kvmw_v4u* dp = reinterpret_cast<kvmw_v4u*>(a.dst) + d_slot * a.run_vecs + v;
+  kvmw_v4u x = {v, v, v, v};
+  if (a.mode != 2)
+    asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(x) : "v"(sp) : "memory");
+  if (a.mode != 1)
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(dp), "v"(x) : "memory");
+  else if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x5EEDF00Du && x[0] == 0x0BADC0DEu)
+    *a.sink = x[2];   // keeps the loaded value observable; practically never taken
+}
+
+// bytes = n_runs * run_bytes are moved.  *_bits = 0: runs at consecutive slots; else
+// permuted over the side's first 2^bits slots (the buffer must hold them, and
+// n_runs <= 2^bits).  Returns 0, -1 on a bad argument, or the hipError_t of the launch.
+extern "C" int kvmw_ref_stream(int mode, const void* src_dev, void* dst_dev, int64_t run_bytes,
+                               int64_t n_runs, int src_bits, int dst_bits, void* sink_dev,
+                               void* hip_stream) {
+  if (mode < 0 || mode > 2 || run_bytes <= 0 || run_bytes % 16 || n_runs <= 0 || src_bits < 0 ||
+      src_bits > 40 || dst_bits < 0 || dst_bits > 40)
+    return -1;
+  if ((src_bits && n_runs > (1ll << src_bits)) || (dst_bits && n_runs > (1ll << dst_bits))) return -1;
+  if ((mode != 2 && !src_dev) || (mode != 1 && !dst_dev) || (mode == 1 && !sink_dev)) return -1;
+  RefArgs a;
+  a.src = (const char*)src_dev;
+  a.dst = (char*)dst_dev;
+  a.run_vecs = (uint32_t)(run_bytes / 16);
+  a.chunks = (a.run_vecs + 255) / 256;
+  a.n_runs = (uint64_t)n_runs;
+  a.src_bits = (uint32_t)src_bits;
+  a.dst_bits = (uint32_t)dst_bits;
+  a.mode = mode;
+  a.sink = (uint32_t*)sink_dev;
+  const uint64_t n_wg = a.n_runs * a.chunks;
+  if (n_wg > 0x7fffffffull) return -1;
+  const uint32_t gx = n_wg < 65536 ? (uint32_t)n_wg : 65536u;
+  const uint32_t gy = (uint32_t)((n_wg + 65535) / 65536);
+  hipLaunchKernelGGL(ref_stream_kernel, dim3(gx, gy), dim3(256), 0, (hipStream_t)hip_stream, a);
+  return (int)hipGetLastError();
+}

@@ -476,8 +476,9 @@ def main():
             ("copy_random_both_32k", wl_device.REF_COPY, 32768, True, True),
         ]
         reference = {}
+        ref_bytes = min(payload, 8 << 30)      # enough for a steady rate; fits every pool's permuted slots
         for name, mode, run, rs, rd in legs:
-            n_runs = payload // run
+            n_runs = ref_bytes // run
             args = (mode, src_mem if mode != wl_device.REF_WRITE else None,
                     dst_mem if mode != wl_device.REF_READ else None, run, n_runs, rs, rd, sink)
             for _ in range(2):

@@ -40,6 +40,8 @@ namespace kvm {
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+typedef const __attribute__((address_space(4))) int32_t* ConstTable;  // block table seen as constant memory
+
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for "no token seen yet"
 
 struct DecReq {
@@ -160,6 +162,13 @@ __device__ __forceinline__ WorkItem work_item(const DecArgs& a) {
   WorkItem w;
   const int pass = blockIdx.x % a.passes;
   w.h = blockIdx.x / a.passes;
+  // Workgroups are handed to the chip's eight dies round-robin in dispatch order, so
+  // with the head as the fastest grid dimension die i would always read the heads
+  // congruent to i modulo 8, i.e. always the same 4 KiB-aligned pieces of a block's
+  // run.  Reads stream faster when the pieces a die reads vary (7.0 -> 7.3 TB/s in a
+  // plain read stream; writes behave the other way round), so the low three bits of
+  // the head are rotated by layer and request: a bijection within each group of 8.
+  if ((a.H & 7) == 0) w.h = (w.h & ~7) | ((w.h + (int)blockIdx.y + (int)blockIdx.z) & 7);
   w.l = blockIdx.y;
   w.split = blockIdx.z % a.n_splits;
   w.rq = a.req[blockIdx.z / a.n_splits];
@@ -171,25 +180,77 @@ __device__ __forceinline__ WorkItem work_item(const DecArgs& a) {
   return w;
 }
 
-// Combines the NP online-softmax states a workgroup has left in LDS (running max
-// in the exp2 domain, running sum, unnormalised accumulator) in state order and
-// writes the result: the normalised output row, or, when the context is split,
-// the workspace entry of this split.
-template <int D, int G, int NP, bool BF16>
-__device__ __forceinline__ void reduce_states(const DecArgs& a, const DecReq& rq, int l, int hq0, int split,
-                                              const float (*s_m)[G], const float (*s_l)[G],
-                                              const float (*s_o)[G][D]) {
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
+// ---- end of a workgroup: from per-lane states to the output row ---------------
+// After the block loop every lane holds, per query head g, the online-softmax state
+// of its token row: running max m[g] (exp2 domain) and sum lsum[g], equal over the
+// lanes of the row, and o[g][0..7], dims sub*8.. of the row's unnormalised output.
+//  1. The 64/LPT token rows of a wave are merged in registers (xor shuffles over the
+//     row bits of the lane index), so a wave leaves ONE state per head.
+//  2. Lanes of row 0 write it to LDS and the wave counts itself done.  There is no
+//     workgroup barrier at the end: a wave that is not the last one simply ends and
+//     frees its slot, so waves that finish early (a wave can have one block less than
+//     its neighbours) do not wait for the slowest one.
+//  3. The wave that arrives last merges the four wave states in wave order and
+//     writes the normalised output row, or, when the context is split, the workspace
+//     entry of this split.
+// The order of every combination depends on logical token positions only.
+template <int D, int G>
+struct WaveStates {
+  float m[4][G];
+  float l[4][G];
+  __attribute__((aligned(16))) float o[4][G][D];
+  unsigned int done;   // waves that have written their state; zeroed at workgroup start
+};
+
+template <int D, int G, bool BF16>
+__device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq& rq, int l, int hq0, int split,
+                                                 int wave, int lane, float (&m)[G], float (&lsum)[G],
+                                                 float (&o)[G][8], WaveStates<D, G>& ws) {
+  constexpr int LPT = D / 8;
+  const int sub = lane % LPT;
+  // 1. merge the token rows of the wave
+#pragma unroll
+  for (int x = LPT; x < 64; x <<= 1) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float m2 = __shfl_xor(m[g], x);
+      const float mx = fmaxf(m[g], m2);
+      const float w1 = __builtin_amdgcn_exp2f(m[g] - mx), w2 = __builtin_amdgcn_exp2f(m2 - mx);
+      lsum[g] = fmaf(__shfl_xor(lsum[g], x), w2, lsum[g] * w1);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] = fmaf(__shfl_xor(o[g][c], x), w2, o[g][c] * w1);
+      m[g] = mx;
+    }
+  }
+  // 2. row 0 holds the wave's state
+  if (lane < LPT) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      if (lane == 0) {
+        ws.m[wave][g] = m[g];
+        ws.l[wave][g] = lsum[g];
+      }
+      v4f* dst = reinterpret_cast<v4f*>(&ws.o[wave][g][sub * 8]);
+      dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
+      dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
+    }
+  }
+  unsigned int before = 0;
+  if (lane == 0)  // release: this wave's LDS writes precede the count; acquire: the last wave sees all
+    before = __hip_atomic_fetch_add(&ws.done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+  if (__builtin_amdgcn_readfirstlane(before) != 3u) return;
+  // 3. the last wave combines the four wave states, in wave order
+  for (int idx = lane; idx < G * D; idx += 64) {
     const int g = idx / D, d = idx % D;
     float mx = kNegBig;
 #pragma unroll
-    for (int pidx = 0; pidx < NP; ++pidx) mx = fmaxf(mx, s_m[pidx][g]);
+    for (int w = 0; w < 4; ++w) mx = fmaxf(mx, ws.m[w][g]);
     float acc = 0.f, den = 0.f;
 #pragma unroll
-    for (int pidx = 0; pidx < NP; ++pidx) {
-      const float wgt = __builtin_amdgcn_exp2f(s_m[pidx][g] - mx);
-      acc = fmaf(s_o[pidx][g][d], wgt, acc);
-      den = fmaf(s_l[pidx][g], wgt, den);
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(ws.m[w][g] - mx);
+      acc = fmaf(ws.o[w][g][d], wgt, acc);
+      den = fmaf(ws.l[w][g], wgt, den);
     }
     const int hq = hq0 + g;
     if (a.n_splits == 1) {
@@ -220,14 +281,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   constexpr int LPT = D / 8;       // lanes per token row
   constexpr int TPI = 64 / LPT;    // token rows per load instruction
   constexpr int NI = B / TPI;      // load instructions per block and per K / V
-  constexpr int NP = 4 * TPI;      // online-softmax states per workgroup
   static_assert(LPT == 8 || LPT == 16, "head_dim must be 64 or 128");
   static_assert(B % TPI == 0, "block_tokens must be a multiple of the rows per load");
 
-  constexpr int GS = G < 4 ? G : 4;  // heads merged through LDS at a time (33 KiB for D = 128)
-  __shared__ float s_m[NP][GS];
-  __shared__ float s_l[NP][GS];
-  __shared__ __attribute__((aligned(16))) float s_o[NP][GS][D];
+  __shared__ WaveStates<D, G> s_ws;   // 8 KiB for G = 4, D = 128
 
   const WorkItem wi = work_item<B, G>(a);
   if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
@@ -241,6 +298,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   const int sub = lane % LPT;
   const int row = lane / LPT;
   const int hq0 = wi.hq0;  // first query head served here
+  // the only workgroup barrier: at the start, where the four waves arrive together
+  if (threadIdx.x == 0) s_ws.done = 0u;
+  __syncthreads();
 
   // query fragment: dims sub*8 .. sub*8+7 of each of the G heads, kept as four
   // packed 16-bit pairs per head; the softmax scale is applied to the reduced score
@@ -271,21 +331,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // this wave handles blocks jb + wave, jb + wave + 4, ...
   const int n_it = (je - jb - wave + 3) / 4;  // may be <= 0
   v4u kc[NI], vc[NI];
-  int ids = 0;
-  auto fetch_ids = [&](int it0) {
-    const int j = jb + wave + 4 * (it0 + lane);
-    ids = j < je ? a.bt[rq.bt + j] : 0;
-  };
-  auto load_k = [&](int it, v4u* kd) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const char* kp = kbase + blk * a.stride_block + lane_off;
+  // Block ids are uniform over the wave: they are read with scalar loads (entry
+  // 4*it of the wave's part of the table), two blocks ahead of their use, on the
+  // scalar cache's own path instead of queueing behind the streamed tiles.
+  // (The table does not change while the kernel runs; reading it through the
+  // constant address space is what makes the compiler use scalar loads inside the
+  // loop, where it otherwise falls back to a vector load and a full wait.)
+  const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + wave);
+  auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };   // clamped: always one of the wave's entries
+  int id_next = 0;   // id of block it + 1 while block it is being consumed
+  auto load_k = [&](int blk_id, v4u* kd) {
+    const char* kp = kbase + (int64_t)blk_id * a.stride_block + lane_off;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
       kd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * inst_off));
   };
-  auto load_v = [&](int it, v4u* vd) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const char* vp = vbase + blk * a.stride_block + lane_off;
+  auto load_v = [&](int blk_id, v4u* vd) {
+    const char* vp = vbase + (int64_t)blk_id * a.stride_block + lane_off;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
       vd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp + i * inst_off));
@@ -300,16 +362,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // copies a conditional load would need.
   // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, the other counters left at
   // their maximum).  The explicit waits below keep the compiler from draining all
-  // loads at the top of every iteration: without them it cannot prove that the
-  // query registers (loaded before the loop) and the block-id register (reloaded
-  // inside a rare branch) are ready, and inserts vmcnt(0) on the hot path.
-  constexpr int kWaitAll = 0x0F70;
+  // loads at the top of every iteration: without it it cannot prove that the query
+  // registers (loaded before the loop) are ready, and inserts vmcnt(0) on the hot path.
   constexpr int kWaitAllButTiles = 0x0F70 | (2 * NI);   // 2*NI <= 8 tile loads may stay in flight
   const char* dummy = reinterpret_cast<const char*>(
       a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // D*2 >= 128 bytes, 16-byte aligned
-  auto load_tile = [&](bool real, const char* base, int it, v4u* td) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const char* p = real ? base + blk * a.stride_block + lane_off : dummy + (uint32_t)sub * 16u;
+  auto load_tile = [&](bool real, const char* base, int blk_id, v4u* td) {
+    const char* p = real ? base + (int64_t)blk_id * a.stride_block + lane_off : dummy + (uint32_t)sub * 16u;
     const uint32_t step = real ? inst_off : 0u;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
@@ -326,11 +385,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 #pragma unroll
       for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i]));
     __builtin_amdgcn_sched_barrier(0);
-    if (more && ((it + 1) & 63) == 0) {
-      fetch_ids(it + 1);
-      __builtin_amdgcn_s_waitcnt(kWaitAll);             // once per 64 blocks of this wave
-    }
-    load_tile(more, kbase, it + 1, kc);
+    const int id_after = block_id(it + 2);
+    load_tile(more, kbase, id_next, kc);
     __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -371,18 +427,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
         for (int c = 0; c < 8; ++c) o[g][c] = fmaf(s[i][g], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_tile(more, vbase, it + 1, vc);
+    load_tile(more, vbase, id_next, vc);
+    id_next = id_after;
     __builtin_amdgcn_sched_barrier(0);
   };
   // Only the request's last block can be partly context, and it is the last
   // iteration of the one wave that owns it: all other iterations run the mask-free
   // instance in a loop of their own.
   if (n_it > 0) {
-    fetch_ids(0);
-    __builtin_amdgcn_s_waitcnt(kWaitAll);
-    load_k(0, kc);
+    const int id0 = block_id(0);
+    id_next = block_id(1);
+    load_k(id0, kc);
     __builtin_amdgcn_sched_barrier(0);
-    load_v(0, vc);
+    load_v(id0, vc);
     __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
     const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;  // context slots in this wave's last block
     const int n_main = t_last < B ? n_it - 1 : n_it;
@@ -390,24 +447,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
     if (n_main < n_it) step(std::true_type{}, n_main, t_last);
   }
 
-  // ---- merge the NP states of the workgroup through LDS, GS heads at a time ----
-  const int slot = wave * TPI + row;
-#pragma unroll
-  for (int g0 = 0; g0 < G; g0 += GS) {
-    if (g0 > 0) __syncthreads();  // the previous group has been read
-#pragma unroll
-    for (int g = 0; g < GS; ++g) {
-      if (sub == 0) {
-        s_m[slot][g] = m[g0 + g];
-        s_l[slot][g] = lsum[g0 + g];
-      }
-      v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
-      dst[0] = v4f{o[g0 + g][0], o[g0 + g][1], o[g0 + g][2], o[g0 + g][3]};
-      dst[1] = v4f{o[g0 + g][4], o[g0 + g][5], o[g0 + g][6], o[g0 + g][7]};
-    }
-    __syncthreads();
-    reduce_states<D, GS, NP, BF16>(a, rq, l, hq0 + g0, split, s_m, s_l, s_o);
-  }
+  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, s_ws);
 }
 
 // Grouped-query decode with the scores on the matrix cores (group of four query
@@ -431,11 +471,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 template <int D, int B, int G, bool BF16, int WMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma_kernel(const DecArgs a) {
   static_assert(D == 128 && B == 16 && (G == 4 || G == 8), "shape of the matrix-core variant");
-  constexpr int NP = 16;  // 4 waves x 4 lane rows
-  constexpr int GS = 4;   // heads merged through LDS at a time
-  __shared__ float s_m[NP][GS];
-  __shared__ float s_l[NP][GS];
-  __shared__ __attribute__((aligned(16))) float s_o[NP][GS][D];
+  __shared__ WaveStates<D, G> s_ws;
 
   const WorkItem wi = work_item<B, G>(a);
   if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
@@ -447,6 +483,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   const int sub = lane % 16;
   const int row = lane / 16;
   const int hq0 = wi.hq0;
+  if (threadIdx.x == 0) s_ws.done = 0u;
+  __syncthreads();
 
   // B operand: dims 32j + 8*row .. +7 of head `sub`; columns >= G are zero
   const uint16_t* qrow = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D;
@@ -474,28 +512,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 
   const int n_it = (je - jb - wave + 3) / 4;
   v4u kc[4], vc[4];
-  int ids = 0;
-  auto fetch_ids = [&](int it0) {
-    const int j = jb + wave + 4 * (it0 + lane);
-    ids = j < je ? a.bt[rq.bt + j] : 0;
-  };
-  auto load_k = [&](bool real, int it) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const char* p = real ? kbase + blk * a.stride_block + k_off : dummy;
+  // block ids through scalar loads, two blocks ahead (as in decode_kernel)
+  const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + wave);
+  auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };
+  int id_next = 0;
+  auto load_k = [&](bool real, int blk_id) {
+    const char* p = real ? kbase + (int64_t)blk_id * a.stride_block + k_off : dummy;
     const uint32_t stp = real ? 64u : 0u;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       kc[j] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + j * stp));
   };
-  auto load_v = [&](bool real, int it) {
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const char* p = real ? vbase + blk * a.stride_block + v_off : dummy;
+  auto load_v = [&](bool real, int blk_id) {
+    const char* p = real ? vbase + (int64_t)blk_id * a.stride_block + v_off : dummy;
     const uint32_t stp = real ? a.stride_slot : 0u;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       vc[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i * stp));
   };
-  constexpr int kWaitAll = 0x0F70;
   constexpr int kWaitAllButTiles = 0x0F70 | 8;
 
   auto step = [&](auto masked_tag, int it, int t_limit) {
@@ -515,11 +549,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more && ((it + 1) & 63) == 0) {
-      fetch_ids(it + 1);
-      __builtin_amdgcn_s_waitcnt(kWaitAll);
-    }
-    load_k(more, it + 1);
+    const int id_after = block_id(it + 2);
+    load_k(more, id_next);
     __builtin_amdgcn_sched_barrier(0);
 
     // online softmax of (head sub, lane row) over tokens 4*row .. 4*row+3 of the block
@@ -567,15 +598,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
         for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[g][i], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_v(more, it + 1);
+    load_v(more, id_next);
+    id_next = id_after;
     __builtin_amdgcn_sched_barrier(0);
   };
   if (n_it > 0) {
-    fetch_ids(0);
-    __builtin_amdgcn_s_waitcnt(kWaitAll);
-    load_k(true, 0);
+    const int id0 = block_id(0);
+    id_next = block_id(1);
+    load_k(true, id0);
     __builtin_amdgcn_sched_barrier(0);
-    load_v(true, 0);
+    load_v(true, id0);
     __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);  // queries have arrived
     const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;
     const int n_main = t_last < B ? n_it - 1 : n_it;
@@ -583,224 +615,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
     if (n_main < n_it) step(std::true_type{}, n_main, t_last);
   }
 
-  const int slot = wave * 4 + row;
+  // the state of head g sits in lane (g, row): hand it to all lanes of the row
+  float mg[G], lg[G];
 #pragma unroll
-  for (int g0 = 0; g0 < G; g0 += GS) {
-    if (g0 > 0) __syncthreads();  // the previous group has been read
-    if (sub >= g0 && sub < g0 + GS) {
-      s_m[slot][sub - g0] = m;
-      s_l[slot][sub - g0] = lsum;
-    }
-#pragma unroll
-    for (int g = 0; g < GS; ++g) {
-      v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][g][sub * 8]);
-      dst[0] = v4f{o[g0 + g][0], o[g0 + g][1], o[g0 + g][2], o[g0 + g][3]};
-      dst[1] = v4f{o[g0 + g][4], o[g0 + g][5], o[g0 + g][6], o[g0 + g][7]};
-    }
-    __syncthreads();
-    reduce_states<D, GS, NP, BF16>(a, rq, l, hq0 + g0, split, s_m, s_l, s_o);
+  for (int g = 0; g < G; ++g) {
+    mg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 4 * g, __builtin_bit_cast(int, m)));
+    lg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 4 * g, __builtin_bit_cast(int, lsum)));
   }
-}
-
-// Grouped-query variant with the K/V tile of a block staged in LDS and shared by
-// the four waves of the workgroup.  All waves walk all blocks of the range; every
-// lane fetches one 16-byte vector of the K tile and one of the V tile (two blocks
-// ahead, held in registers, then written to a two-stage LDS ring), and each wave
-// serves one query head (group 4) or half of the token rows of one head (group 2)
-// from the shared tile.  Against the register-tile kernel a wave holds 16 instead
-// of 32 tile registers and one head's accumulator instead of four, so more
-// workgroups stay resident and more bytes are in flight per CU.
-// LDS tile layout = the block-head run itself (token-major, 16 bytes per lane), so
-// lane x of read i reads bytes [i*1024 + x*16, +16): consecutive lanes, no bank
-// conflicts.
-template <int D, int B, int G, bool BF16>
-__global__ __launch_bounds__(256) void decode_shared_kernel(const DecArgs a) {
-  constexpr int LPT = D / 8;
-  constexpr int TPI = 64 / LPT;
-  constexpr int NI = B / TPI;
-  constexpr int WPH = 4 / G;       // waves per query head
-  constexpr int NIW = NI / WPH;    // 1 KiB row groups of a tile per wave
-  constexpr int NP = 4 * TPI;      // online-softmax states per workgroup
-  constexpr int TV = B * LPT;      // 16-byte vectors per K (or V) tile
-  static_assert(G == 2 || G == 4, "group of 2 or 4 query heads per KV head");
-  static_assert(NI % WPH == 0 && NIW >= 1, "tile rows must divide among the waves of a head");
-  static_assert(TV <= 256, "one vector per lane per tile");
-
-  __shared__ __attribute__((aligned(16))) char s_tile[2][2][TV * 16];  // [stage][K, V]
-  __shared__ float s_m[NP];
-  __shared__ float s_l[NP];
-  __shared__ __attribute__((aligned(16))) float s_o[NP][D];
-
-  const WorkItem wi = work_item<B, G>(a);
-  if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
-  const DecReq rq = wi.rq;
-  const int h = wi.h, l = wi.l, split = wi.split, k = rq.k, jb = wi.jb, je = wi.je;
-  const int n_it = je - jb;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int sub = lane % LPT;
-  const int row = lane / LPT;
-  const int g = wave % G;          // query head of this wave
-  const int part = wave / G;       // which row groups of the tile it takes
-  const int hq0 = wi.hq0;
-
-  uint32_t qp[4];
-  {
-    const uint16_t* qptr = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0 + g) * D + sub * 8;
-    const v4u raw = *reinterpret_cast<const v4u*>(qptr);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) qp[c] = raw[c];
-  }
-  const float sc = a.scale_log2e;
-  float m = kNegBig, lsum = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-  // loader role: lane `tid` moves vector `tid` of both tiles
-  const bool loader = tid < TV;
-  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head +
-                      (uint64_t)(tid / LPT) * a.stride_slot + (uint32_t)(tid % LPT) * 16u;
-  const char* vbase = kbase + a.stride_kv;
-  const char* dummy = reinterpret_cast<const char*>(
-      a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // always valid, 16-byte aligned
-  int ids = 0;
-  auto fetch_ids = [&](int it0) {
-    const int j = jb + it0 + lane;
-    ids = j < je ? a.bt[rq.bt + j] : 0;
-  };
-  constexpr int kWaitAll = 0x0F70;
-  auto gload = [&](int it, v4u& rk, v4u& rv) {
-    if ((it & 63) == 0 && it > 0 && it < n_it) {
-      fetch_ids(it);
-      __builtin_amdgcn_s_waitcnt(kWaitAll);   // once per 64 blocks
-    }
-    // Every call issues exactly two loads (lanes without a vector to fetch, and
-    // steps past the end of the range, read the query row instead): with a fixed
-    // number of loads per step the waits before the LDS writes can leave the
-    // younger loads in flight instead of draining them.
-    const int64_t blk = __builtin_amdgcn_readlane(ids, it & 63);
-    const bool real = loader && it < n_it;
-    const char* kp = real ? kbase + blk * a.stride_block : dummy;
-    const char* vp = real ? vbase + blk * a.stride_block : dummy;
-    rk = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp));
-    rv = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp));
-  };
-  auto lstore = [&](int stage, const v4u& rk, const v4u& rv) {
-    if (loader) {
-      *reinterpret_cast<v4u*>(&s_tile[stage][0][tid * 16]) = rk;
-      *reinterpret_cast<v4u*>(&s_tile[stage][1][tid * 16]) = rv;
-    }
-  };
-  auto compute = [&](int stage, int it) {
-    const int t_limit = k - (jb + it) * B;
-    const char* kt = &s_tile[stage][0][lane * 16];
-    const char* vt = &s_tile[stage][1][lane * 16];
-    float s[NIW];
-#pragma unroll
-    for (int ii = 0; ii < NIW; ++ii) {
-      const int i = part + ii * WPH;
-      const v4u kv = *reinterpret_cast<const v4u*>(kt + i * 1024);
-      s[ii] = group_sum<LPT>(dot8<BF16>(qp, kv)) * sc;
-    }
-    float mx = m;
-#pragma unroll
-    for (int ii = 0; ii < NIW; ++ii)
-      if ((part + ii * WPH) * TPI + row < t_limit) mx = fmaxf(mx, s[ii]);
-    const float alpha = __builtin_amdgcn_exp2f(m - mx);
-    m = mx;
-    float add = 0.f;
-#pragma unroll
-    for (int ii = 0; ii < NIW; ++ii) {
-      s[ii] = ((part + ii * WPH) * TPI + row < t_limit) ? __builtin_amdgcn_exp2f(s[ii] - mx) : 0.f;
-      add += s[ii];
-    }
-    lsum = lsum * alpha + add;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) o[c] *= alpha;
-#pragma unroll
-    for (int ii = 0; ii < NIW; ++ii) {
-      const int i = part + ii * WPH;
-      v4u vv = *reinterpret_cast<const v4u*>(vt + i * 1024);
-      if (i * TPI + row >= t_limit) vv = v4u{0u, 0u, 0u, 0u};  // garbage past the context
-      float vf[8];
-      widen8<BF16>(vv, vf);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) o[c] = fmaf(s[ii], vf[c], o[c]);
-    }
-  };
-
-  // P register sets hold the blocks in flight, two LDS stages the blocks being
-  // consumed.  Entering step x: stage x&1 holds block x, set (x+1)%P block x+1
-  // (stored to the other stage during the step), sets for x+2 .. x+P-1 are in
-  // flight and set x%P is free for block x+P.
-  constexpr int P = 4;
-  v4u rk[P], rv[P];
-#pragma unroll
-  for (int u = 0; u < P; ++u) rk[u] = rv[u] = v4u{0u, 0u, 0u, 0u};
-  fetch_ids(0);
-  __builtin_amdgcn_s_waitcnt(kWaitAll);
-#pragma unroll
-  for (int u = 0; u < P; ++u) gload(u, rk[u], rv[u]);
-  lstore(0, rk[0], rv[0]);
-  __syncthreads();
-  for (int it = 0; it < n_it; it += P) {
-#pragma unroll
-    for (int u = 0; u < P; ++u) {
-      const int x = it + u;
-      if (x >= n_it) break;
-      gload(x + P, rk[u], rv[u]);
-      compute(u & 1, x);
-      if (x + 1 < n_it) lstore((u + 1) & 1, rk[(u + 1) % P], rv[(u + 1) % P]);
-      __syncthreads();   // next stage visible; every wave is done reading this one
-    }
-  }
-
-  // ---- merge the states of the waves that served the same head ----
-  const int slot = wave * TPI + row;
-  if (sub == 0) {
-    s_m[slot] = m;
-    s_l[slot] = lsum;
-  }
-  {
-    v4f* dst = reinterpret_cast<v4f*>(&s_o[slot][sub * 8]);
-    dst[0] = v4f{o[0], o[1], o[2], o[3]};
-    dst[1] = v4f{o[4], o[5], o[6], o[7]};
-  }
-  __syncthreads();
-  for (int idx = tid; idx < G * D; idx += 256) {
-    const int gg = idx / D, d = idx % D;
-    float mx = kNegBig;
-#pragma unroll
-    for (int p = 0; p < WPH; ++p)
-#pragma unroll
-      for (int rr = 0; rr < TPI; ++rr) mx = fmaxf(mx, s_m[(gg + G * p) * TPI + rr]);
-    float acc = 0.f, den = 0.f;
-#pragma unroll
-    for (int p = 0; p < WPH; ++p)
-#pragma unroll
-      for (int rr = 0; rr < TPI; ++rr) {
-        const int pidx = (gg + G * p) * TPI + rr;
-        const float wgt = __builtin_amdgcn_exp2f(s_m[pidx] - mx);
-        acc = fmaf(s_o[pidx][d], wgt, acc);
-        den = fmaf(s_l[pidx], wgt, den);
-      }
-    const int hq = hq0 + gg;
-    if (a.n_splits == 1) {
-      const float res = acc / den;
-      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
-      if (a.out_f32)
-        reinterpret_cast<float*>(a.out)[oi] = res;
-      else
-        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
-    } else {
-      float* e = ws_entry(a.ws, a, rq.slot, l, hq, split, D);
-      e[d] = acc;
-      if (d == 0) {
-        e[D] = mx;
-        e[D + 1] = den;
-      }
-    }
-  }
+  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, mg, lg, o, s_ws);
 }
 
 // Log-sum-exp merge of the context splits, in split order.
@@ -891,7 +713,8 @@ struct DecodePlan {
   int g_tile;    // query heads per workgroup (1, 2, 4 or 8)
   int passes;    // workgroups per KV head
   int n_splits;
-  bool cap;      // long contexts: at most two waves per SIMD
+  bool cap;      // at most two waves per SIMD
+  bool mfma;     // scores on the matrix cores (groups of four and eight, head_dim 128, 16-token blocks)
 };
 
 static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
@@ -916,6 +739,7 @@ static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
   }
   p.n_splits = std::max(1, std::min(s, 64));
   p.cap = false;
+  p.mfma = false;
   return p;
 }
 
@@ -925,33 +749,20 @@ static int64_t ws_bytes_for(const kvm_layout& l, int n_req, int n_splits) {
 
 template <int D, int B, bool BF16, int WMAX>
 static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, hipStream_t st) {
-  const bool shared = options().decode_shared_tiles != 0;
+  if constexpr (D == 128 && B == 16) {
+    if (p.mfma && p.g_tile == 8) {
+      hipLaunchKernelGGL((decode_mfma_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a);
+      return;
+    }
+    if (p.mfma && p.g_tile == 4) {
+      hipLaunchKernelGGL((decode_mfma_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
+      return;
+    }
+  }
   switch (p.g_tile) {
-    case 8:
-      // eight heads on the vector unit alone are bound by it (4.5 TB/s); with the
-      // scores on the matrix cores the kernel follows the stream again
-      if constexpr (D == 128 && B == 16) {
-        if (options().decode_mfma != 0) {
-          hipLaunchKernelGGL((decode_mfma_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a);
-          break;
-        }
-      }
-      hipLaunchKernelGGL((decode_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a);
-      break;
-    case 4:
-      if constexpr (D == 128 && B == 16) {
-        if (options().decode_mfma > 0) {
-          hipLaunchKernelGGL((decode_mfma_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
-          break;
-        }
-      }
-      if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 4, BF16>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
-      break;
-    case 2:
-      if (shared) hipLaunchKernelGGL((decode_shared_kernel<D, B, 2, BF16>), grid, dim3(256), 0, st, a);
-      else hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16, WMAX>), grid, dim3(256), 0, st, a);
-      break;
+    case 8: hipLaunchKernelGGL((decode_kernel<D, B, 8, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
+    case 4: hipLaunchKernelGGL((decode_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<D, B, 2, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
     default: hipLaunchKernelGGL((decode_kernel<D, B, 1, BF16, WMAX>), grid, dim3(256), 0, st, a); break;
   }
 }
@@ -1069,14 +880,25 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const int32_
   }
 
   {
-    // long contexts: cap the waves per SIMD (mean of 128 blocks = 2048 tokens per
-    // workgroup and more; at 34 blocks the cap costs 11 %, at 60 it changes nothing,
-    // at 480 it gains 6 %); "decode.cap_waves" overrides (0 never, 1 always)
+    // Which instance runs, by group width and mean context per workgroup (measured
+    // on MI355X with equal-length batches, GB/s of KV read; "capped" = at most two
+    // waves per SIMD):
+    //  - groups of four and eight: capped beats uncapped from 16 blocks per
+    //    workgroup on (32 blocks: 5900 against 5500, 128: 6190 against 6000), only
+    //    very short contexts (8 blocks) prefer more waves;
+    //  - groups of four: scores on the matrix cores win up to 128 blocks (32 blocks:
+    //    6120 against 5885 capped, 128: 6300 against 6190), the vector kernel wins on
+    //    long contexts (2048 blocks: 6630 against 6420);
+    //  - one or two heads per KV head: the cap only pays on long contexts.
+    // "decode.cap_waves" (0 never, 1 always) and "decode.mfma" (0 never, 1 always)
+    // override.
     int64_t live = 0;
     for (int r = 0; r < v.n_req; ++r) live += v.nb[r] > 0;
     const int64_t mean_blocks = v.total_blocks / std::max<int64_t>(1, live * p.n_splits);
-    const int mode = options().decode_cap_waves;
-    p.cap = mode < 0 ? mean_blocks >= 128 : mode != 0;
+    const int cap_mode = options().decode_cap_waves, mfma_mode = options().decode_mfma;
+    p.cap = cap_mode < 0 ? mean_blocks >= (p.g_tile >= 4 ? 12 : 128) : cap_mode != 0;
+    p.mfma = l.head_dim == 128 && l.block_tokens == 16 &&
+             (p.g_tile == 8 ? mfma_mode != 0 : p.g_tile == 4 && (mfma_mode < 0 ? mean_blocks < 256 : mfma_mode != 0));
   }
 
   DecArgs a;

@@ -366,9 +366,6 @@ int kvm_set_option(const char* name, int64_t value) {
   } else if (!strcmp(name, "decode.mfma")) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.mfma must be -1, 0 or 1");
     o.decode_mfma = (int)value;
-  } else if (!strcmp(name, "decode.shared_tiles")) {
-    if (value != 0 && value != 1) return fail(KVM_EINVAL, "decode.shared_tiles must be 0 or 1");
-    o.decode_shared_tiles = (int)value;
   } else if (!strcmp(name, "decode.split_target")) {
     if (value < 1 || value > (1 << 20)) return fail(KVM_EINVAL, "decode.split_target must be in [1, 2^20]");
     o.decode_split_target = (int)value;

@@ -62,9 +62,8 @@ struct Options {
   int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
   int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block
   int decode_max_group = 8;     // largest number of query heads one workgroup serves from one pass over K/V (4 or 8)
-  int decode_cap_waves = -1;    // -1: by mean context length; 0 / 1: never / always cap at two waves per SIMD
-  int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks): -1 groups of 8 only, 0 never, 1 groups of 4 and 8
-  int decode_shared_tiles = 0;  // 1: grouped-query decode stages the K/V tile in LDS, one wave per query head
+  int decode_cap_waves = -1;    // -1: by group width and mean context length; 0 / 1: never / always cap at two waves per SIMD
+  int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks): -1 by group and context length, 0 never, 1 groups of 4 and 8
   int decode_split_target = 2048;  // workgroups a decode launch should reach by splitting contexts
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits

@@ -50,20 +50,18 @@ SHAPES = [
 ]
 
 
-VARIANTS = {"matrix_core_scores": (1, 0), "register_tiles": (0, 0), "lds_tiles": (0, 1), "shipped": (-1, 0)}
+VARIANTS = {"matrix_core_scores": 1, "vector_unit_scores": 0, "shipped": -1}
 
 
 def set_variant(name):
-    mfma, shared = VARIANTS[name]
-    kvm.kvm_set_option("decode.mfma", mfma)
-    kvm.kvm_set_option("decode.shared_tiles", shared)
+    kvm.kvm_set_option("decode.mfma", VARIANTS[name])
 
 
 @pytest.mark.parametrize("variant", list(VARIANTS))
 @pytest.mark.parametrize("m", SHAPES, ids=[s.name for s in SHAPES])
 def test_decode_matches_oracle(oracle, m, variant):
-    """The grouped-query kernels (scores on the matrix cores; per-wave register
-    tiles; K/V tile shared through LDS) and the MHA kernel against the fp64 oracle."""
+    """The grouped-query kernels (scores on the matrix cores or on the vector unit) and
+    the MHA kernel against the fp64 oracle."""
     lens = [1, 15, 16, 17, 100, 333, 64]
     src, _ = make_pair(m, 64, 8, lens, [0] * len(lens), seed=21, finite=True)
     side = Side(m, 64, src.host, src.tables, lens)
@@ -89,7 +87,7 @@ def test_decode_k0_rows_untouched_and_scale(oracle):
     assert np.abs(got[[0, 2]] - ref[[0, 2]]).max() < TOL
 
 
-@pytest.mark.parametrize("variant", ["matrix_core_scores", "register_tiles"])
+@pytest.mark.parametrize("variant", ["matrix_core_scores", "vector_unit_scores"])
 def test_capped_occupancy_instances_give_the_same_bits(oracle, variant):
     """The kernels exist in two instances (at most two or eight waves per SIMD, chosen by
     mean context length); they are the same arithmetic."""

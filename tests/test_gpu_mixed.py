@@ -6,7 +6,7 @@ compared bit for bit with the CPU oracle carrying out the same orders, tables
 included, and every order's decode output is compared with the fp64 oracle.
 Full-size case (243 GiB arena, 512 requests, 200 orders, staged 16 per flush as the
 benchmark runs them): every order's decode output equals decode over the source
-bit for bit and a sampled row of it matches the fp64 oracle; at the end EVERY block
+to fp32 rounding (1e-5) and a sampled row of it matches the fp64 oracle; at the end EVERY block
 of every live request holds the generator's bytes of the block it started in
 (compared on the device, partly filled last blocks through the CPU oracle on the
 host), position-sensitive hashes show that blocks never handed out are unchanged,
@@ -256,8 +256,12 @@ def test_mixed_pool_full_size(oracle):
         if k == 0:
             continue
         m = sc.models[rq.model]
-        assert torch.equal(out_dst[rq.model][oi], out_src[rq.model][oi]), \
-            "order %d: decode over destination != decode over source" % oi
+        # the destination was decoded together with the other orders of its flush, the
+        # source alone: the library may pick another split count or kernel instance
+        # for the two batches, so the rows agree to fp32 rounding, not bit for bit
+        # (with the same batch on both sides they are bit-equal: test_gpu_fullsize.py)
+        diff = float((out_dst[rq.model][oi] - out_src[rq.model][oi]).abs().max())
+        assert diff < 1e-5, "order %d: decode over destination differs from decode over source by %g" % (oi, diff)
         # one sampled (layer, query head) row against the fp64 oracle on regenerated K/V
         l, hq = int(rng.integers(m.L)), int(rng.integers(m.Hq))
         g = hq // (m.Hq // m.H)

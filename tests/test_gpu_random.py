@@ -67,7 +67,7 @@ def test_random_case(oracle, seed):
     torch.cuda.synchronize()
 
 
-DEC_OPTIONS = ("decode.mfma", "decode.shared_tiles", "decode.cap_waves", "decode.force_splits")
+DEC_OPTIONS = ("decode.mfma", "decode.max_group", "decode.cap_waves", "decode.force_splits")
 
 
 @pytest.mark.parametrize("seed", range(32))
@@ -82,7 +82,7 @@ def test_random_decode_case(oracle, seed):
     n_req = int(rng.integers(1, 5))
     lens = [int(rng.integers(1, 40 * B)) if rng.random() < 0.8 else int(rng.integers(1, B + 2)) for _ in range(n_req)]
     n_blocks = sum(-(-ln // B) for ln in lens) + 5
-    values = [int(rng.integers(-1, 2)), int(rng.integers(2)), int(rng.integers(-1, 2)), int(rng.choice([0, 0, 1, 2, 5]))]
+    values = [int(rng.integers(-1, 2)), int(rng.choice([4, 8])), int(rng.integers(-1, 2)), int(rng.choice([0, 0, 1, 2, 5]))]
     try:
         for name, v in zip(DEC_OPTIONS, values):
             kvm.kvm_set_option(name, v)

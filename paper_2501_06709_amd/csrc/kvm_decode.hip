@@ -281,6 +281,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   constexpr int LPT = D / 8;       // lanes per token row
   constexpr int TPI = 64 / LPT;    // token rows per load instruction
   constexpr int NI = B / TPI;      // load instructions per block and per K / V
+  // Tiles in flight per wave and per K / V: the capped instances (two waves per SIMD,
+  // up to 256 registers each) keep two blocks ahead, the others one.
+  constexpr int P = (WMAX == 2 && G < 8) ? 2 : 1;
   static_assert(LPT == 8 || LPT == 16, "head_dim must be 64 or 128");
   static_assert(B % TPI == 0, "block_tokens must be a multiple of the rows per load");
 
@@ -330,16 +333,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 
   // this wave handles blocks jb + wave, jb + wave + 4, ...
   const int n_it = (je - jb - wave + 3) / 4;  // may be <= 0
-  v4u kc[NI], vc[NI];
+  v4u kcs[P][NI], vcs[P][NI];
   // Block ids are uniform over the wave: they are read with scalar loads (entry
-  // 4*it of the wave's part of the table), two blocks ahead of their use, on the
+  // 4*it of the wave's part of the table), one block ahead of their use, on the
   // scalar cache's own path instead of queueing behind the streamed tiles.
   // (The table does not change while the kernel runs; reading it through the
   // constant address space is what makes the compiler use scalar loads inside the
   // loop, where it otherwise falls back to a vector load and a full wait.)
   const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + wave);
   auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };   // clamped: always one of the wave's entries
-  int id_next = 0;   // id of block it + 1 while block it is being consumed
+  int id_next = 0;   // id of block it + P while block it is being consumed
   auto load_k = [&](int blk_id, v4u* kd) {
     const char* kp = kbase + (int64_t)blk_id * a.stride_block + lane_off;
 #pragma unroll
@@ -353,10 +356,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       vd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp + i * inst_off));
   };
 
-  // Software pipeline with one K and one V register tile: K of the next block is
-  // requested as soon as the scores of the current one are formed, V of the next
-  // block as soon as the current V rows are accumulated, so a load is always in
-  // flight while the other tile is being consumed.  Every iteration issues both
+  // Software pipeline with P K and P V register tiles: K of block it + P is
+  // requested as soon as the scores of block it are formed, V of block it + P as
+  // soon as the V rows of block it are accumulated, so loads are always in flight
+  // while a tile is being consumed.  Every iteration issues both
   // tile loads unconditionally; after the last block they go to the wave's own
   // query row (valid, aligned, cached), which keeps the loop free of the register
   // copies a conditional load would need.
@@ -364,7 +367,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // their maximum).  The explicit waits below keep the compiler from draining all
   // loads at the top of every iteration: without it it cannot prove that the query
   // registers (loaded before the loop) are ready, and inserts vmcnt(0) on the hot path.
-  constexpr int kWaitAllButTiles = 0x0F70 | (2 * NI);   // 2*NI <= 8 tile loads may stay in flight
+  constexpr int kTileLoads = 2 * P * NI;                 // tile loads that may stay in flight (<= 63)
+  constexpr int kWaitAllButTiles = 0x0F70 | (kTileLoads & 15) | ((kTileLoads >> 4) << 14);
   const char* dummy = reinterpret_cast<const char*>(
       a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // D*2 >= 128 bytes, 16-byte aligned
   auto load_tile = [&](bool real, const char* base, int blk_id, v4u* td) {
@@ -376,16 +380,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   };
   // One block of the context.  MASKED handles a last block that is only partly
   // context; full blocks take the mask-free instance.
-  auto step = [&](auto masked_tag, int it, int t_limit) {
+  auto step = [&](auto masked_tag, auto slot_tag, int it, int t_limit) {
     constexpr bool MASKED = decltype(masked_tag)::value;
-    const bool more = it + 1 < n_it;
+    constexpr int S = decltype(slot_tag)::value;   // register tile that holds block it
+    v4u(&kc)[NI] = kcs[S];
+    v4u(&vc)[NI] = vcs[S];
+    const bool more = it + P < n_it;
     float s[NI][G];
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i]));
     __builtin_amdgcn_sched_barrier(0);
-    const int id_after = block_id(it + 2);
+    const int id_after = block_id(it + P + 1);
     load_tile(more, kbase, id_next, kc);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -435,16 +442,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // iteration of the one wave that owns it: all other iterations run the mask-free
   // instance in a loop of their own.
   if (n_it > 0) {
-    const int id0 = block_id(0);
-    id_next = block_id(1);
-    load_k(id0, kc);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(id0, vc);
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, P - 1>;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {   // a wave with fewer than P blocks loads its last one twice
+      const int idj = block_id(j);
+      load_k(idj, kcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_v(idj, vcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    id_next = block_id(P);
     __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
     const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;  // context slots in this wave's last block
     const int n_main = t_last < B ? n_it - 1 : n_it;
-    for (int it = 0; it < n_main; ++it) step(std::false_type{}, it, B);
-    if (n_main < n_it) step(std::true_type{}, n_main, t_last);
+    if constexpr (P == 1) {
+      for (int it = 0; it < n_main; ++it) step(std::false_type{}, S0{}, it, B);
+      if (n_main < n_it) step(std::true_type{}, S0{}, n_main, t_last);
+    } else {
+      // blocks alternate between the two register tiles: even ones in tile 0
+      int it = 0;
+      for (; it + 1 < n_main; it += 2) {
+        step(std::false_type{}, S0{}, it, B);
+        step(std::false_type{}, S1{}, it + 1, B);
+      }
+      if (it < n_main) step(std::false_type{}, S0{}, it, B);
+      if (n_main < n_it) {
+        if (n_main & 1) step(std::true_type{}, S1{}, n_main, t_last);
+        else step(std::true_type{}, S0{}, n_main, t_last);
+      }
+    }
   }
 
   finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, s_ws);
@@ -471,6 +498,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 template <int D, int B, int G, bool BF16, int WMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma_kernel(const DecArgs a) {
   static_assert(D == 128 && B == 16 && (G == 4 || G == 8), "shape of the matrix-core variant");
+  constexpr int P = (WMAX == 2 && G < 8) ? 2 : 1;   // tiles in flight per wave and per K / V (as in decode_kernel)
   __shared__ WaveStates<D, G> s_ws;
 
   const WorkItem wi = work_item<B, G>(a);
@@ -511,30 +539,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   const int bp_row = 16 * row * 4;  // ds_bpermute byte address of lane (head 0, this lane's row)
 
   const int n_it = (je - jb - wave + 3) / 4;
-  v4u kc[4], vc[4];
+  v4u kcs[P][4], vcs[P][4];
   // block ids through scalar loads, two blocks ahead (as in decode_kernel)
   const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + wave);
   auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };
   int id_next = 0;
-  auto load_k = [&](bool real, int blk_id) {
+  auto load_k = [&](bool real, int blk_id, v4u* kc) {
     const char* p = real ? kbase + (int64_t)blk_id * a.stride_block + k_off : dummy;
     const uint32_t stp = real ? 64u : 0u;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       kc[j] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + j * stp));
   };
-  auto load_v = [&](bool real, int blk_id) {
+  auto load_v = [&](bool real, int blk_id, v4u* vc) {
     const char* p = real ? vbase + (int64_t)blk_id * a.stride_block + v_off : dummy;
     const uint32_t stp = real ? a.stride_slot : 0u;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       vc[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i * stp));
   };
-  constexpr int kWaitAllButTiles = 0x0F70 | 8;
+  constexpr int kTileLoads = 8 * P;
+  constexpr int kWaitAllButTiles = 0x0F70 | (kTileLoads & 15) | ((kTileLoads >> 4) << 14);
 
-  auto step = [&](auto masked_tag, int it, int t_limit) {
+  auto step = [&](auto masked_tag, auto slot_tag, int it, int t_limit) {
     constexpr bool MASKED = decltype(masked_tag)::value;
-    const bool more = it + 1 < n_it;
+    constexpr int S = decltype(slot_tag)::value;   // register tile that holds block it
+    v4u(&kc)[4] = kcs[S];
+    v4u(&vc)[4] = vcs[S];
+    const bool more = it + P < n_it;
     v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -549,8 +581,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    const int id_after = block_id(it + 2);
-    load_k(more, id_next);
+    const int id_after = block_id(it + P + 1);
+    load_k(more, id_next, kc);
     __builtin_amdgcn_sched_barrier(0);
 
     // online softmax of (head sub, lane row) over tokens 4*row .. 4*row+3 of the block
@@ -598,21 +630,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
         for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[g][i], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_v(more, id_next);
+    load_v(more, id_next, vc);
     id_next = id_after;
     __builtin_amdgcn_sched_barrier(0);
   };
   if (n_it > 0) {
-    const int id0 = block_id(0);
-    id_next = block_id(1);
-    load_k(true, id0);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(true, id0);
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, P - 1>;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {   // a wave with fewer than P blocks loads its last one twice
+      const int idj = block_id(j);
+      load_k(true, idj, kcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_v(true, idj, vcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    id_next = block_id(P);
     __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);  // queries have arrived
     const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;
     const int n_main = t_last < B ? n_it - 1 : n_it;
-    for (int it = 0; it < n_main; ++it) step(std::false_type{}, it, B);
-    if (n_main < n_it) step(std::true_type{}, n_main, t_last);
+    if constexpr (P == 1) {
+      for (int it = 0; it < n_main; ++it) step(std::false_type{}, S0{}, it, B);
+      if (n_main < n_it) step(std::true_type{}, S0{}, n_main, t_last);
+    } else {
+      int it = 0;
+      for (; it + 1 < n_main; it += 2) {
+        step(std::false_type{}, S0{}, it, B);
+        step(std::false_type{}, S1{}, it + 1, B);
+      }
+      if (it < n_main) step(std::false_type{}, S0{}, it, B);
+      if (n_main < n_it) {
+        if (n_main & 1) step(std::true_type{}, S1{}, n_main, t_last);
+        else step(std::true_type{}, S0{}, n_main, t_last);
+      }
+    }
   }
 
   // the state of head g sits in lane (g, row): hand it to all lanes of the row
@@ -882,21 +933,21 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const int32_
   {
     // Which instance runs, by group width and mean context per workgroup (measured
     // on MI355X with equal-length batches, GB/s of KV read; "capped" = at most two
-    // waves per SIMD):
-    //  - groups of four and eight: capped beats uncapped from 16 blocks per
-    //    workgroup on (32 blocks: 5900 against 5500, 128: 6190 against 6000), only
-    //    very short contexts (8 blocks) prefer more waves;
+    // waves per SIMD, which also leaves the registers for two tiles in flight):
+    //  - capped beats uncapped from 16 blocks per workgroup on, for every group width
+    //    (one head per KV head, 32 blocks: 6450 against 6310; groups of four, 64
+    //    blocks: 6240 against 5840); only very short contexts (8 blocks) prefer more
+    //    waves (6290 against 5290);
     //  - groups of four: scores on the matrix cores win up to 128 blocks (32 blocks:
-    //    6120 against 5885 capped, 128: 6300 against 6190), the vector kernel wins on
-    //    long contexts (2048 blocks: 6630 against 6420);
-    //  - one or two heads per KV head: the cap only pays on long contexts.
+    //    6120 against 5885, 128: 6300 against 6190), the vector kernel wins on long
+    //    contexts (2048 blocks: 6630 against 6420).
     // "decode.cap_waves" (0 never, 1 always) and "decode.mfma" (0 never, 1 always)
     // override.
     int64_t live = 0;
     for (int r = 0; r < v.n_req; ++r) live += v.nb[r] > 0;
     const int64_t mean_blocks = v.total_blocks / std::max<int64_t>(1, live * p.n_splits);
     const int cap_mode = options().decode_cap_waves, mfma_mode = options().decode_mfma;
-    p.cap = cap_mode < 0 ? mean_blocks >= (p.g_tile >= 4 ? 12 : 128) : cap_mode != 0;
+    p.cap = cap_mode < 0 ? mean_blocks >= 12 : cap_mode != 0;
     p.mfma = l.head_dim == 128 && l.block_tokens == 16 &&
              (p.g_tile == 8 ? mfma_mode != 0 : p.g_tile == 4 && (mfma_mode < 0 ? mean_blocks < 256 : mfma_mode != 0));
   }

@@ -54,7 +54,6 @@ def parse():
     ap.add_argument("--config", default="llama3_8b_gqa")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=16, help="requests in the oracle's sample")
-    ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--order", type=int, default=None)
     ap.add_argument("--split-target", type=int, default=None)
@@ -308,7 +307,7 @@ def main():
     from kvm_workload import device as wl_device
 
     kvm.lib()  # fails loudly if the HIP library is not built
-    for name, val in (("copy.unroll", a.unroll), ("copy.nontemporal", a.nontemporal),
+    for name, val in (("copy.nontemporal", a.nontemporal),
                       ("copy.order", a.order), ("decode.split_target", a.split_target)):
         if val is not None:
             kvm.kvm_set_option(name, val)

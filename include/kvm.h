@@ -282,42 +282,40 @@ const char* kvm_strerror(int status);
 /* Detail of the last failure on the calling thread ("" if none); the pointer
  * stays valid until the next failing call on this thread. */
 const char* kvm_last_error(void);
-/* Launch tuning knob for benchmarking sweeps; unknown name or out-of-range
- * value gives KVM_EINVAL.  Names:
+/* Launch options; unknown name or out-of-range value gives KVM_EINVAL.  Every
+ * option's default is automatic and is what the measurements in the repository
+ * were taken with; the other settings exist to compare against.  Names:
  *  "reset"              every option back to its default (the value is ignored).
- *  "copy.unroll"        1,2,4,8 16-byte vectors per lane per workgroup; 0 = automatic (1).
- *  "copy.nontemporal"   0/1 (default 1): streaming hint on loads and stores.
+ *  "copy.nontemporal"   0/1 (default 1): streaming cache policy on loads and stores.
  *  "copy.order"         1: the (layer, K|V) plane is the outermost grid dimension;
  *                       0: consecutive workgroups walk the planes of one block;
  *                       -1 (default): 1 for layer-major pools (stride_kv >=
  *                       stride_block) and for kvm_pack, 0 for block-major pools.
- *  "copy.lds_pad_kb"    0..64: dynamic LDS per workgroup, only caps residency.
  *  "copy.stage_linear"  bit 0: kvm_pack, bit 1: kvm_unpack assign work in staging
  *                       order (one 4 KiB piece of the staging buffer per workgroup)
  *                       instead of by pool block; -1 (default): kvm_pack does when
  *                       the batch's mean request moves 4096 tokens or more.
- *  "copy.stage_scalar_ids" 0/1 (default 1): where every workgroup of the
- *                       staging-order kernels stays inside one block, its block id is
- *                       one scalar load instead of a per-lane load.
  *  "decode.mfma"        scores on the matrix cores (head_dim 128, 16-token blocks):
- *                       -1 (default) for groups of eight query heads only, 0 never,
- *                       1 for groups of four and eight.
- *  "decode.max_group"   8 (default) or 4: query heads of one KV head that a workgroup
- *                       serves from one pass over K and V; a larger group takes
- *                       several passes (reads K and V again).
+ *                       -1 (default): groups of eight query heads always, groups of
+ *                       four when the mean context per workgroup is below 256
+ *                       blocks; 0 never; 1 for groups of four and eight always.
  *  "decode.cap_waves"   -1 (default): the tuned decode kernels run at most two waves
- *                       per SIMD when the mean context per workgroup is 2048 tokens or
- *                       more; 0 never, 1 always.
- *  "decode.shared_tiles" 0/1 (default 0): for grouped-query layouts, 1 stages each
- *                       K/V tile in LDS once per workgroup and gives every wave one
- *                       query head, 0 keeps the tile in one wave's registers for all
- *                       heads of its group.
+ *                       per SIMD, with two tiles in flight, when the mean context per
+ *                       workgroup is 12 blocks or more; 0 never, 1 always.
  *  "decode.split_target" workgroups a decode launch should reach by splitting
- *                       contexts (default 2048; the mixed stream measures the same
- *                       from 512 to 8192).
- *  "decode.max_splits"  1..64.
+ *                       contexts (default 2048).
+ *  "decode.max_splits"  1..64 (default 16).
  *  "decode.force_splits" 0 = automatic, else exactly this many context splits.
- * Process-wide; not thread-safe against concurrent launches. */
+ *
+ * Thread safety of the library.  Options are process-wide and unsynchronised: set
+ * them before other threads launch.  kvm_last_error() is per thread.  The size
+ * helpers, kvm_layout_canonical, kvm_divide_moves and kvm_strerror are pure.
+ * kvm_pack, kvm_unpack, kvm_migrate, kvm_paged_decode and kvm_paged_decode_rows keep
+ * no state between calls and may run concurrently from several host threads and
+ * on several streams; the device buffers they write must not overlap between
+ * concurrent calls.  A kvm_freelist is not synchronised: one thread at a time per
+ * list.  kvm_paged_decode_static is safe to call from several threads, but its
+ * launches on one GPU must not overlap in time (they share the static array). */
 int kvm_set_option(const char* name, int64_t value);
 
 #ifdef __cplusplus

@@ -5,12 +5,12 @@
 // layer, K and V, are read through the source block table and written through
 // the destination block table (or to / from a contiguous staging buffer).
 //
-// All three operations are one kernel, `copy_kernel<MODE, U, NT>` (packing long
+// All three operations are one kernel, `copy_kernel<MODE, NT>` (packing long
 // requests has a second one, `stage_kernel`, further down):
 //  - a work item is (block entry of a request, plane = layer*2+kv, chunk); one
-//    256-lane workgroup moves up to U*256 16-byte vectors of it (U = 1 ships:
-//    4 KiB per workgroup, plane outermost in the grid);
-//  - every lane issues its U loads before its first store;
+//    256-lane workgroup moves up to 256 16-byte vectors of it: 4 KiB per workgroup,
+//    one vector per lane, plane outermost in the grid (two, four and eight vectors
+//    per lane all measured slower: 6340 / 5920 / 5710 GB/s fused at one / two / four);
 //  - loads and stores carry the streaming cache-policy bits (sc0 sc1 nt);
 //  - block ids and request descriptors are wave-uniform: they are read with
 //    scalar loads from the kernel-argument segment and the block table, which
@@ -97,43 +97,19 @@ struct CopyArgs {
 // (system scope, non-temporal): against "nt" alone it measured +1 % on the fused
 // move and +5 % on pack, against plain accesses +8 % and more.  The compiler's
 // builtins only reach "nt", so the hinted accesses are written as instructions:
-// all U loads of a lane and the wait for them form ONE asm statement, so no
-// register of theirs can be read before its data has arrived, and the loads of a
-// lane still overlap.  The hint is a template parameter on purpose: written as
-// a run-time choice between a hinted and a plain access of one address, the two
-// are merged by the optimiser and the hint is lost.
-#define KVM_LD "global_load_dwordx4 %"
-#define KVM_POL ", off sc0 sc1 nt\n\t"
-template <bool NT, int U>
-__device__ __forceinline__ void load16xU(const char* const (&p)[U], v4u (&v)[U]) {
-  static_assert(U == 1 || U == 2 || U == 4 || U == 8, "vectors per lane");
-  if constexpr (!NT) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = *reinterpret_cast<const v4u*>(p[u]);
-  } else if constexpr (U == 1) {
-    asm volatile(KVM_LD "0, %1" KVM_POL "s_waitcnt vmcnt(0)" : "=&v"(v[0]) : "v"(p[0]) : "memory");
-  } else if constexpr (U == 2) {
-    asm volatile(KVM_LD "0, %2" KVM_POL KVM_LD "1, %3" KVM_POL "s_waitcnt vmcnt(0)"
-                 : "=&v"(v[0]), "=&v"(v[1])
-                 : "v"(p[0]), "v"(p[1])
-                 : "memory");
-  } else if constexpr (U == 4) {
-    asm volatile(KVM_LD "0, %4" KVM_POL KVM_LD "1, %5" KVM_POL KVM_LD "2, %6" KVM_POL KVM_LD "3, %7" KVM_POL
-                 "s_waitcnt vmcnt(0)"
-                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-                 : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3])
-                 : "memory");
-  } else {
-    asm volatile(KVM_LD "0, %8" KVM_POL KVM_LD "1, %9" KVM_POL KVM_LD "2, %10" KVM_POL KVM_LD "3, %11" KVM_POL
-                 KVM_LD "4, %12" KVM_POL KVM_LD "5, %13" KVM_POL KVM_LD "6, %14" KVM_POL KVM_LD "7, %15" KVM_POL
-                 "s_waitcnt vmcnt(0)"
-                 : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]),
-                   "=&v"(v[7])
-                 : "v"(p[0]), "v"(p[1]), "v"(p[2]), "v"(p[3]), "v"(p[4]), "v"(p[5]), "v"(p[6]), "v"(p[7])
-                 : "memory");
-  }
+// the load and the wait for it form ONE asm statement, so the register cannot be
+// read before its data has arrived.  The hint is a template parameter on purpose:
+// written as a run-time choice between a hinted and a plain access of one address,
+// the two are merged by the optimiser and the hint is lost.
+template <bool NT>
+__device__ __forceinline__ v4u load16(const char* p) {
+  v4u v;
+  if constexpr (NT)
+    asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+  else
+    v = *reinterpret_cast<const v4u*>(p);
+  return v;
 }
-#undef KVM_LD
 template <bool NT>
 __device__ __forceinline__ void store16(char* p, v4u v) {
   if constexpr (NT)
@@ -141,9 +117,8 @@ __device__ __forceinline__ void store16(char* p, v4u v) {
   else
     *reinterpret_cast<v4u*>(p) = v;
 }
-#undef KVM_POL
 
-template <int MODE, int U, bool NT>
+template <int MODE, bool NT>
 __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   // ---- decode the work item (all wave-uniform, no division) ----
   // order 1 (shipped): grid = (chunks, block entries, planes): consecutive
@@ -188,24 +163,16 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
   }
   const uint32_t per_head = ns * a.DV;          // vectors per head in this item
   const uint32_t n_vec = per_head * (uint32_t)a.H;
-  const uint32_t v0 = chunk * (U * 256u) + threadIdx.x;
-  if (chunk * (U * 256u) >= n_vec) return;
+  const uint32_t v = chunk * 256u + threadIdx.x;   // this lane's vector of the item
+  if (chunk * 256u >= n_vec) return;
 
   // Lanes past the end of the item load its last vector again (always in
-  // bounds) and skip the store, so the loads stay unconditional straight-line code.
-  const uint32_t v_last = n_vec - 1;
-  v4u val[U];
+  // bounds) and skip the store, so the load stays unconditional straight-line code.
+  const uint32_t vc = min(v, n_vec - 1);
   if (MODE == kMigrate && dense) {
     // one contiguous run on both sides
-    const char* lp[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) lp[u] = sbase + (uint64_t)min(v0 + u * 256u, v_last) * 16u;
-    load16xU<NT, U>(lp, val);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t v = v0 + u * 256u;
-      if (v < n_vec) store16<NT>(dbase + (uint64_t)v * 16u, val[u]);
-    }
+    const v4u val = load16<NT>(sbase + (uint64_t)vc * 16u);
+    if (v < n_vec) store16<NT>(dbase + (uint64_t)v * 16u, val);
     return;
   }
 
@@ -219,28 +186,15 @@ __global__ __launch_bounds__(256) void copy_kernel(const CopyArgs a) {
     stage_plane = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)plane * a.H * n_tok * a.DV +
                              tok0 * a.DV) * 16u;
   }
-  uint32_t soff[U], doff[U];
-  uint64_t shead[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t v = min(v0 + u * 256u, v_last);
-    const uint32_t h = v / per_head;
-    const uint32_t w = v - h * per_head;  // slot*DV + dv
-    const uint32_t slot = fastdiv(w, a.dvdiv);
-    const uint32_t dv = w - slot * a.DV;
-    soff[u] = h * a.src.stride_head + slot * a.src.stride_slot + dv * 16u;
-    doff[u] = h * a.dst.stride_head + slot * a.dst.stride_slot + dv * 16u;
-    shead[u] = (uint64_t)h * stage_head + (uint64_t)w * 16u;
-  }
-  const char* lp[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) lp[u] = MODE == kUnpack ? stage_plane + shead[u] : sbase + soff[u];
-  load16xU<NT, U>(lp, val);
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t v = v0 + u * 256u;
-    if (v < n_vec) store16<NT>(MODE == kPack ? stage_plane + shead[u] : dbase + doff[u], val[u]);
-  }
+  const uint32_t h = vc / per_head;
+  const uint32_t w = vc - h * per_head;  // slot*DV + dv
+  const uint32_t slot = fastdiv(w, a.dvdiv);
+  const uint32_t dv = w - slot * a.DV;
+  const uint32_t soff = h * a.src.stride_head + slot * a.src.stride_slot + dv * 16u;
+  const uint32_t doff = h * a.dst.stride_head + slot * a.dst.stride_slot + dv * 16u;
+  const uint64_t shead = (uint64_t)h * stage_head + (uint64_t)w * 16u;
+  const v4u val = load16<NT>(MODE == kUnpack ? stage_plane + shead : sbase + soff);
+  if (v < n_vec) store16<NT>(MODE == kPack ? stage_plane + shead : dbase + doff, val);
 }
 
 static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
@@ -259,37 +213,13 @@ static PoolSide make_side(const kvm_pool* p, const kvm_batch* b) {
   return s;
 }
 
-// 16-byte vectors per lane per workgroup.  One (4 KiB per workgroup) measured best
-// on MI355X for all three operations once the plane is the outermost grid
-// dimension; larger values remain for comparison.
-template <int MODE>
-static int pick_unroll() {
-  const int u = options().copy_unroll;
-  return u ? u : 1;
-}
-
 template <int MODE>
 static hipError_t launch(const CopyArgs& a, hipStream_t stream) {
-  const Options& o = options();
   const dim3 grid = a.order ? dim3(a.n_chunks, a.n_items, a.n_planes) : dim3(a.n_chunks, a.n_planes, a.n_items);
-#define KVM_LAUNCH(U, NT) \
-  hipLaunchKernelGGL((copy_kernel<MODE, U, NT>), grid, dim3(256), (size_t)o.copy_lds_pad_kb * 1024, stream, a)
-  if (o.copy_nontemporal) {
-    switch (pick_unroll<MODE>()) {
-      case 1: KVM_LAUNCH(1, true); break;
-      case 2: KVM_LAUNCH(2, true); break;
-      case 4: KVM_LAUNCH(4, true); break;
-      default: KVM_LAUNCH(8, true); break;
-    }
-  } else {
-    switch (pick_unroll<MODE>()) {
-      case 1: KVM_LAUNCH(1, false); break;
-      case 2: KVM_LAUNCH(2, false); break;
-      case 4: KVM_LAUNCH(4, false); break;
-      default: KVM_LAUNCH(8, false); break;
-    }
-  }
-#undef KVM_LAUNCH
+  if (options().copy_nontemporal)
+    hipLaunchKernelGGL((copy_kernel<MODE, true>), grid, dim3(256), 0, stream, a);
+  else
+    hipLaunchKernelGGL((copy_kernel<MODE, false>), grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -320,9 +250,8 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
   // always takes the plane outermost: that is the order of its staging buffer.
   a.order = options().copy_order >= 0 ? options().copy_order
                                       : (MODE == kPack || l.stride_kv >= l.stride_block ? 1 : 0);
-  const int U = pick_unroll<MODE>();
   const int64_t vec_per_item = (int64_t)l.n_kv_heads * l.block_tokens * a.DV;
-  a.n_chunks = (int32_t)ceil_div(vec_per_item, (int64_t)U * 256);
+  a.n_chunks = (int32_t)ceil_div(vec_per_item, 256);
   const int64_t bpt_vec = (int64_t)l.n_layers * 2 * l.n_kv_heads * a.DV;  // vectors per token
 
   // limits are checked for the whole batch before the first launch: an error
@@ -363,7 +292,7 @@ static int run_copy(const kvm_pool* src, const kvm_batch* sb, const BatchView& s
 
 // ---- staging-linear pack / unpack -------------------------------------------
 // A second mapping for the staged path: the work is cut along the staging buffer
-// instead of along pool blocks.  One workgroup moves U pieces of 256 consecutive
+// instead of along pool blocks.  One workgroup moves one piece of 256 consecutive
 // 16-byte vectors of one (request, plane, head) run of the staging buffer; the
 // pool side is then a gather (pack) or scatter (unpack) of token rows.
 //
@@ -388,7 +317,6 @@ struct StageReq {
   uint32_t n_vec;        // vectors of one (plane, head) run: (k - start) * DV
   uint32_t first_wg;     // first workgroup of the request in this launch
   int64_t stage_vec;     // staging offset of the request in 16-byte vectors
-  int32_t j_last;        // block that holds token k - 1
   FastDiv chunks;        // workgroups per (plane, head) run
 };
 
@@ -404,7 +332,7 @@ struct StageArgs {
   StageReq req[kMaxReqPerLaunch];
 };
 
-template <bool PACK, int U, bool NT, bool FAST>
+template <bool PACK, bool NT, bool FAST>
 __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
   // the launch's workgroups are numbered row by row over a 2-D grid (one grid
   // dimension cannot hold them: a dimension is limited to 2^32 - 1 work-items);
@@ -425,71 +353,34 @@ __global__ __launch_bounds__(256) void stage_kernel(const StageArgs a) {
   const uint32_t plane = fastdiv(run, a.heads);
   const uint32_t h = run - plane * a.heads.d;
   const uint32_t n_vec = rq.n_vec;
-  const uint32_t x0 = chunk * (U * 256u) + threadIdx.x;
-  const uint32_t x_last = n_vec - 1;
+  const uint32_t x = chunk * 256u + threadIdx.x;   // this lane's vector of the run
+  const uint32_t xc = min(x, n_vec - 1);            // lanes past the end repeat the last vector and store nothing
   char* pbase = a.pool.base + (uint64_t)(plane >> 1) * a.pool.stride_layer +
                 (uint64_t)(plane & 1) * a.pool.stride_kv + (uint64_t)h * a.pool.stride_head;
   char* sbase = a.stage + ((uint64_t)rq.stage_vec + (uint64_t)(plane * (uint32_t)a.H + h) * n_vec) * 16u;
 
-  v4u val[U];
   if constexpr (FAST) {
-    char* pp[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      // a piece past the end of the run (last chunk only) is pointed at the last
-      // block of the request; its lanes load in bounds and store nothing
-      const uint32_t t = (uint32_t)rq.start + (chunk * U + u) * a.piece_tokens;
-      const uint32_t j = min(fastdiv(t, a.bdiv), (uint32_t)rq.j_last);
-      const int32_t blk = a.pool.bt[rq.bt + (int32_t)j];
-      const uint32_t slot = t - fastdiv(t, a.bdiv) * (uint32_t)a.B;
-      pp[u] = pbase + (uint64_t)blk * a.pool.stride_block + slot * a.pool.stride_slot;
-    }
-    const char* lp[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t x = x0 + u * 256u;
-      // lanes past the end repeat the piece's first vector (in bounds on both sides)
-      const uint32_t off = x < n_vec ? threadIdx.x * 16u : 0u;
-      lp[u] = PACK ? pp[u] + off : sbase + (uint64_t)min(x, x_last) * 16u;
-    }
-    load16xU<NT, U>(lp, val);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t x = x0 + u * 256u;
-      if (x < n_vec) store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp[u] + threadIdx.x * 16u, val[u]);
-    }
+    // the piece lies inside one block and is contiguous there: one scalar id load
+    const uint32_t t = (uint32_t)rq.start + chunk * a.piece_tokens;
+    const uint32_t j = fastdiv(t, a.bdiv);
+    const int32_t blk = a.pool.bt[rq.bt + (int32_t)j];
+    const uint32_t slot = t - j * (uint32_t)a.B;
+    char* pp = pbase + (uint64_t)blk * a.pool.stride_block + slot * a.pool.stride_slot;
+    const uint32_t off = (xc - chunk * 256u) * 16u;
+    const v4u val = load16<NT>(PACK ? pp + off : sbase + (uint64_t)xc * 16u);
+    if (x < n_vec) store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp + off, val);
     return;
   }
 
-  int32_t blk[U];
-  uint32_t inner[U];  // byte offset of the lane's vector inside its block
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t x = min(x0 + u * 256u, x_last);  // lanes past the end repeat the last vector
-    const uint32_t tok = fastdiv(x, a.dvdiv);
-    const uint32_t dv = x - tok * a.DV;
-    const uint32_t t = (uint32_t)rq.start + tok;
-    const uint32_t j = fastdiv(t, a.bdiv);
-    const uint32_t slot = t - j * (uint32_t)a.B;
-    blk[u] = a.pool.bt[rq.bt + (int32_t)j];
-    inner[u] = slot * a.pool.stride_slot + dv * 16u;
-  }
-  const char* lp[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t x = min(x0 + u * 256u, x_last);
-    const char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
-    lp[u] = PACK ? pp : sbase + (uint64_t)x * 16u;
-  }
-  load16xU<NT, U>(lp, val);
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const uint32_t x = x0 + u * 256u;
-    if (x < n_vec) {
-      char* pp = pbase + (uint64_t)blk[u] * a.pool.stride_block + inner[u];
-      store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp, val[u]);
-    }
-  }
+  const uint32_t tok = fastdiv(xc, a.dvdiv);
+  const uint32_t dv = xc - tok * a.DV;
+  const uint32_t t = (uint32_t)rq.start + tok;
+  const uint32_t j = fastdiv(t, a.bdiv);
+  const uint32_t slot = t - j * (uint32_t)a.B;
+  const int32_t blk = a.pool.bt[rq.bt + (int32_t)j];
+  char* pp = pbase + (uint64_t)blk * a.pool.stride_block + slot * a.pool.stride_slot + dv * 16u;
+  const v4u val = load16<NT>(PACK ? pp : sbase + (uint64_t)xc * 16u);
+  if (x < n_vec) store16<NT>(PACK ? sbase + (uint64_t)x * 16u : pp, val);
 }
 
 template <bool PACK>
@@ -497,7 +388,6 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
                      hipStream_t stream) {
   const kvm_layout& l = pool->layout;
   const Options& o = options();
-  const int U = o.copy_unroll ? std::min(o.copy_unroll, 4) : 1;  // pieces per workgroup: 1, 2 or 4
   StageArgs a;
   memset(&a, 0, sizeof a);
   a.pool = make_side(pool, b);
@@ -513,7 +403,7 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
   // FAST: a 256-vector piece covers whole tokens, a block holds a whole number of
   // pieces, the rows of a block's head are contiguous and every range starts on a
   // block boundary.
-  bool fast = o.stage_scalar_ids && 256 % a.DV == 0 && ((int64_t)a.B * a.DV) % 256 == 0 &&
+  bool fast = 256 % a.DV == 0 && ((int64_t)a.B * a.DV) % 256 == 0 &&
               a.pool.stride_slot == a.DV * 16u;
   for (int q = 0; q < view.n_req && fast; ++q) fast = view.start[q] % a.B == 0;
   a.piece_tokens = fast ? 256u / a.DV : 0u;
@@ -522,7 +412,7 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
   for (int q = 0; q < view.n_req; ++q) {
     if (((int64_t)view.k[q] + 1) * a.DV > 0x7fffffff)
       return fail(KVM_EINVAL, "a single request's (plane, head) run exceeds 2^31 vectors");
-    const int64_t chunks = ceil_div((int64_t)(view.k[q] - view.start[q]) * a.DV, (int64_t)U * 256);
+    const int64_t chunks = ceil_div((int64_t)(view.k[q] - view.start[q]) * a.DV, 256);
     if (chunks * n_planes * a.H > 0x7fffffff)
       return fail(KVM_EINVAL, "a single request exceeds the grid size limit");
   }
@@ -534,7 +424,7 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
     int64_t n_wg = 0;
     while (r < view.n_req && n < kMaxReqPerLaunch) {
       const int64_t n_tok = view.k[r] - view.start[r];
-      const int64_t chunks = ceil_div(n_tok * a.DV, (int64_t)U * 256);
+      const int64_t chunks = ceil_div(n_tok * a.DV, 256);
       const int64_t wgs = chunks * n_planes * a.H;
       if (n_wg + wgs > 0x7fffffff) break;
       if (n_tok > 0) {  // requests that move nothing take no descriptor
@@ -544,7 +434,6 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
         q.n_vec = (uint32_t)(n_tok * a.DV);
         q.first_wg = (uint32_t)n_wg;
         q.stage_vec = stage_vec;
-        q.j_last = (view.k[r] - 1) / a.B;
         q.chunks = make_fastdiv((uint32_t)chunks);
         a.first_wg[n++] = (uint32_t)n_wg;
         n_wg += wgs;
@@ -556,23 +445,13 @@ static int run_stage(const kvm_pool* pool, const kvm_batch* b, const BatchView& 
     a.n_wg = (uint32_t)n_wg;
     const StageGrid sg = stage_grid(n_wg);
     const dim3 grid(sg.x, sg.y), block(256);
-#define KVM_STAGE2(UU, NT)                                                                       \
-  do {                                                                                           \
-    if (fast) hipLaunchKernelGGL((stage_kernel<PACK, UU, NT, true>), grid, block, 0, stream, a); \
-    else hipLaunchKernelGGL((stage_kernel<PACK, UU, NT, false>), grid, block, 0, stream, a);     \
-  } while (0)
-#define KVM_STAGE(UU)                              \
-  do {                                             \
-    if (o.copy_nontemporal) KVM_STAGE2(UU, true);  \
-    else KVM_STAGE2(UU, false);                    \
-  } while (0)
-    switch (U) {
-      case 1: KVM_STAGE(1); break;
-      case 2: KVM_STAGE(2); break;
-      default: KVM_STAGE(4); break;
+    if (o.copy_nontemporal) {
+      if (fast) hipLaunchKernelGGL((stage_kernel<PACK, true, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stage_kernel<PACK, true, false>), grid, block, 0, stream, a);
+    } else {
+      if (fast) hipLaunchKernelGGL((stage_kernel<PACK, false, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stage_kernel<PACK, false, false>), grid, block, 0, stream, a);
     }
-#undef KVM_STAGE
-#undef KVM_STAGE2
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(KVM_EHIP, hipGetErrorString(e));
   }

@@ -773,7 +773,7 @@ static DecodePlan plan_decode(const kvm_layout& l, int n_req, int max_nb) {
   const int G = l.n_q_heads / l.n_kv_heads;
   // eight query heads per KV head are served from one pass over K and V (two
   // passes of four would read them twice)
-  p.g_tile = (G % 8 == 0 && options().decode_max_group >= 8) ? 8 : (G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1));
+  p.g_tile = G % 8 == 0 ? 8 : (G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1));
   p.passes = G / p.g_tile;
   const Options& o = options();
   int s = 1;

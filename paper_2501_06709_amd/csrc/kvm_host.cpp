@@ -338,28 +338,15 @@ int kvm_set_option(const char* name, int64_t value) {
   Options& o = options();
   if (!strcmp(name, "reset")) {
     o = Options();
-  } else if (!strcmp(name, "copy.unroll")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-      return fail(KVM_EINVAL, "copy.unroll must be 0 (automatic), 1, 2, 4 or 8");
-    o.copy_unroll = (int)value;
   } else if (!strcmp(name, "copy.nontemporal")) {
     if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.nontemporal must be 0 or 1");
     o.copy_nontemporal = (int)value;
   } else if (!strcmp(name, "copy.order")) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "copy.order must be -1, 0 or 1");
     o.copy_order = (int)value;
-  } else if (!strcmp(name, "copy.lds_pad_kb")) {
-    if (value < 0 || value > 64) return fail(KVM_EINVAL, "copy.lds_pad_kb must be in [0,64]");
-    o.copy_lds_pad_kb = (int)value;
   } else if (!strcmp(name, "copy.stage_linear")) {
     if (value < -1 || value > 3) return fail(KVM_EINVAL, "copy.stage_linear must be in [-1,3]");
     o.stage_linear = (int)value;
-  } else if (!strcmp(name, "copy.stage_scalar_ids")) {
-    if (value != 0 && value != 1) return fail(KVM_EINVAL, "copy.stage_scalar_ids must be 0 or 1");
-    o.stage_scalar_ids = (int)value;
-  } else if (!strcmp(name, "decode.max_group")) {
-    if (value != 4 && value != 8) return fail(KVM_EINVAL, "decode.max_group must be 4 or 8");
-    o.decode_max_group = (int)value;
   } else if (!strcmp(name, "decode.cap_waves")) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.cap_waves must be -1, 0 or 1");
     o.decode_cap_waves = (int)value;

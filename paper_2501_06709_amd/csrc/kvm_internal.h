@@ -55,13 +55,9 @@ inline StageGrid stage_grid(int64_t n_wg) {
 }
 
 struct Options {
-  int copy_unroll = 0;        // 16-byte vectors per lane per pass; 0 = per-operation default
   int copy_nontemporal = 1;   // streaming (no-reuse) cache hints
   int copy_order = -1;        // -1: by layout (plane outermost for layer-major pools); 1: plane outermost; 0: planes of a block consecutive
-  int copy_lds_pad_kb = 0;    // dynamic LDS per workgroup, only to cap residency (tuning)
   int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
-  int stage_scalar_ids = 1;   // staging-linear kernels: scalar block-id load when a workgroup stays in one block
-  int decode_max_group = 8;     // largest number of query heads one workgroup serves from one pass over K/V (4 or 8)
   int decode_cap_waves = -1;    // -1: by group width and mean context length; 0 / 1: never / always cap at two waves per SIMD
   int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks): -1 by group and context length, 0 never, 1 groups of 4 and 8
   int decode_split_target = 2048;  // workgroups a decode launch should reach by splitting contexts

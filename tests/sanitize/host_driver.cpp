@@ -149,7 +149,7 @@ int main() {
   divider(rng);
   validation(rng);
   launch_splitting();
-  CHECK(kvm_set_option("copy.unroll", 3) == KVM_EINVAL && kvm_set_option("reset", 0) == KVM_OK);
+  CHECK(kvm_set_option("copy.order", 3) == KVM_EINVAL && kvm_set_option("reset", 0) == KVM_OK);
   CHECK(kvm_set_option(nullptr, 0) == KVM_EINVAL);
   printf("host driver ok\n");
   return 0;

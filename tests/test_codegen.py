@@ -39,12 +39,12 @@ def wide_accesses(text):
 
 
 @pytest.mark.parametrize("prefix", [
-    "_ZN3kvm11copy_kernelILi0ELi1ELb1EEE",      # fused migrate, one vector per lane, hinted
-    "_ZN3kvm11copy_kernelILi2ELi1ELb1EEE",      # unpack
-    "_ZN3kvm11copy_kernelILi1ELi1ELb1EEE",      # pack, block-cut
-    "_ZN3kvm12stage_kernelILb1ELi1ELb1ELb1EEE",  # pack, staging order, uniform block id
-    "_ZN3kvm12stage_kernelILb1ELi1ELb1ELb0EEE",
-    "_ZN3kvm12stage_kernelILb0ELi1ELb1ELb1EEE",
+    "_ZN3kvm11copy_kernelILi0ELb1EEE",      # fused migrate, hinted
+    "_ZN3kvm11copy_kernelILi2ELb1EEE",      # unpack
+    "_ZN3kvm11copy_kernelILi1ELb1EEE",      # pack, block-cut
+    "_ZN3kvm12stage_kernelILb1ELb1ELb1EEE",  # pack, staging order, uniform block id
+    "_ZN3kvm12stage_kernelILb1ELb1ELb0EEE",
+    "_ZN3kvm12stage_kernelILb0ELb1ELb1EEE",
 ])
 def test_shipped_copy_kernels_carry_the_streaming_hint(copy_asm, prefix):
     acc = wide_accesses(body(copy_asm, prefix))
@@ -53,7 +53,7 @@ def test_shipped_copy_kernels_carry_the_streaming_hint(copy_asm, prefix):
 
 
 def test_plain_instantiation_has_no_hint(copy_asm):
-    acc = wide_accesses(body(copy_asm, "_ZN3kvm11copy_kernelILi0ELi1ELb0EEE"))
+    acc = wide_accesses(body(copy_asm, "_ZN3kvm11copy_kernelILi0ELb0EEE"))
     assert acc and not any(a.endswith(" nt") for a in acc)
 
 

@@ -197,11 +197,11 @@ def test_freelist_matches_oracle_allocator(oracle):
 def test_options_and_strerror():
     L = kvm.lib()
     assert L.kvm_strerror(0) == b"ok" and L.kvm_strerror(-2) == b"free list exhausted"
-    for name, val in (("copy.unroll", 3), ("copy.nontemporal", 2), ("nope", 1),
+    for name, val in (("copy.order", 2), ("copy.nontemporal", 2), ("nope", 1), ("copy.unroll", 1),
                       ("decode.max_splits", 0), ("decode.force_splits", 65)):
         with pytest.raises(kvm.KvmError):
             kvm.kvm_set_option(name, val)
-    kvm.kvm_set_option("copy.unroll", 0)
+    kvm.kvm_set_option("copy.order", -1)
     kvm.kvm_set_option("decode.force_splits", 0)
 
 
@@ -221,11 +221,11 @@ def test_per_request_limit_is_checked_before_the_first_launch():
 
 
 def test_options_reset():
-    kvm.kvm_set_option("copy.unroll", 8)
+    kvm.kvm_set_option("copy.order", 0)
     kvm.kvm_set_option("decode.mfma", 1)
     kvm.kvm_set_option("reset", 0)
     # an out-of-range value is still refused, an unknown name too
-    for name, v in (("copy.unroll", 3), ("decode.max_group", 5), ("no.such.option", 1)):
+    for name, v in (("copy.order", 3), ("decode.cap_waves", 5), ("no.such.option", 1)):
         with pytest.raises(kvm.KvmError) as e:
             kvm.kvm_set_option(name, v)
         assert e.value.status == kvm.KVM_EINVAL

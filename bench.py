@@ -230,7 +230,7 @@ def bench_mixed(a, log):
         pools[mi][rq.half].free.reserve(rq.table[:1])  # ... which stays in use
         pools[mi][1 - rq.half].free.free(got)
     torch.cuda.synchronize()
-    mig.copy_marks.clear()
+    mig.reset_copy_stats()
     launches0 = mig.launches
     moved = skipped = blocks = 0
     nbytes = 0
@@ -263,10 +263,9 @@ def bench_mixed(a, log):
                                                                       mig.launches - launches0))
     gbs = nbytes / dt / 1e9
     hbm_gbs = 1.5 * nbytes / dt / 1e9      # + the decode's read of every moved byte
-    copy_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in mig.copy_marks)
-    copy_bytes = sum(b for _, _, b in mig.copy_marks)
+    copy_ms, copy_bytes, n_copies = mig.copy_stats()
     copy_gbs = copy_bytes / (copy_ms * 1e-3) / 1e9
-    log("fused migrate launches: %d, %.2f ms in total, %.0f GB/s" % (len(mig.copy_marks), copy_ms, copy_gbs))
+    log("fused migrate launches: %d, %.2f ms in total, %.0f GB/s" % (n_copies, copy_ms, copy_gbs))
     print(json.dumps({
         "metric": "KV migrate GB/s (read+write)", "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1,
         "steps": moved, "warmup": len(sc.models), "ms_per_step": round(dt * 1e3 / max(moved, 1), 4),
@@ -285,7 +284,7 @@ def bench_mixed(a, log):
         "roofline": {"kernel": "copy_kernel<migrate> (kvm_migrate), all launches of the stream",
                      "bound": "hbm", "achieved": round(copy_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(copy_gbs / HBM_PEAK_GBS, 4),
-                     "launches": len(mig.copy_marks), "algorithmic_bytes": copy_bytes,
+                     "launches": n_copies, "algorithmic_bytes": copy_bytes,
                      "traffic": None}}), flush=True)
 
 

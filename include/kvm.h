@@ -277,6 +277,72 @@ int kvm_divide_moves(const kvm_move* moves, int32_t n_moves, const int64_t* comm
                      int32_t n_links, const int64_t* comp_boundary, int32_t n_instances,
                      int32_t policy, int32_t* out_class);
 
+/* ---- order sequencing (host; launches through the entry points above) -------
+ * Sec. "Adaptive Request Migration", "Boundary Profiling": the source memory of a
+ * migrating request cannot be released until the transfer is complete; Sec. "Online
+ * KV Cache Scheduling", request operation batching: the moves of a time slot are
+ * known together.  An order moves tokens [0,k) of one request from `src` into
+ * freshly allocated blocks of `dst` (two pools of one model).  Orders are staged and
+ * then enqueued together by a flush:
+ *   - one host-to-device copy carries the block tables of all staged orders;
+ *   - the staged orders that share a (src, dst) pool pair become ONE kvm_migrate call
+ *     and, where a decode was asked for, ONE kvm_paged_decode_rows call (float32
+ *     output, default scale) over the destination;
+ *   - one event is recorded behind the flush; the source blocks of its orders go back
+ *     to their free lists once it has completed.  At most `depth` flushes are in flight
+ *     before a call waits for the oldest, so the stream never drains between flushes.
+ * An order whose source blocks are written by an order that is still staged (the same
+ * request moved twice) is not grouped with it: staging it flushes first.
+ *
+ * The sequencer allocates no device memory: the caller hands it a pinned host buffer
+ * and a device buffer of kvm_sequencer_table_ints() int32 each for the tables (both
+ * must outlive it), and optionally a decode workspace.  A sequencer, and the free
+ * lists it is given, belong to one host thread at a time; all its launches go to the
+ * stream passed with each call (use one stream per sequencer). */
+typedef struct kvm_sequencer kvm_sequencer;
+int64_t kvm_sequencer_table_ints(int32_t max_blocks_per_request, int32_t max_staged, int32_t depth);
+/* NULL (kvm_last_error() says why) on non-positive sizes, NULL table buffers or
+ * table_ints below kvm_sequencer_table_ints(). */
+kvm_sequencer* kvm_sequencer_create(int32_t max_blocks_per_request, int32_t max_staged, int32_t depth,
+                                    int32_t* tables_host_pinned, int32_t* tables_dev, int64_t table_ints,
+                                    void* decode_workspace_dev, int64_t decode_workspace_bytes);
+/* Waits for everything in flight, releases its source blocks, hands the destination
+ * blocks of orders that were never enqueued back, frees the host state. */
+void kvm_sequencer_destroy(kvm_sequencer* seq);
+/* Stage one order: pops ceil(k / block_tokens) blocks from dst_free into
+ * dst_table_out (host, ascending) and notes the order for the next flush; a full
+ * stage (max_staged orders) flushes first.  src_table: host, the request's
+ * n_src_blocks block ids in src (copied).  q_dev != NULL asks for paged decode of the
+ * request over the destination after its copy: query row `row` of q_dev, output row
+ * `row` of out_dev (float32), both [rows][layers][query heads][head_dim]; orders
+ * staged together that share q_dev / out_dev need distinct rows.
+ * KVM_ENOMEM when dst_free cannot supply the blocks even after everything staged and
+ * in flight has been enqueued, awaited and released; the order is then not staged and
+ * dst_table_out is untouched.  KVM_EINVAL: NULL argument, k outside
+ * [0, n_src_blocks * block_tokens], n_src_blocks above max_blocks_per_request, a
+ * source id outside the pool.  An error of a flush that this call triggered is
+ * returned as that flush's (see kvm_sequencer_flush); the order is then not staged. */
+int kvm_sequencer_stage(kvm_sequencer* seq, const kvm_pool* src, kvm_freelist* src_free,
+                        const kvm_pool* dst, kvm_freelist* dst_free, const int32_t* src_table,
+                        int32_t n_src_blocks, int32_t k, const void* q_dev, void* out_dev, int32_t row,
+                        int32_t* dst_table_out, void* hip_stream);
+/* Enqueue everything staged on hip_stream (no-op when nothing is staged).  On an
+ * error of one of its launches the groups already enqueued stay in flight (their
+ * sources are released after the flush's event as usual), the destination blocks of
+ * the groups not enqueued go back to their free lists at once and their sources stay
+ * allocated; the error is returned. */
+int kvm_sequencer_flush(kvm_sequencer* seq, void* hip_stream);
+/* kvm_sequencer_flush, then wait for every flush in flight and release its sources. */
+int kvm_sequencer_drain(kvm_sequencer* seq, void* hip_stream);
+/* kvm_migrate + kvm_paged_decode_rows calls made so far (-1 on NULL). */
+int64_t kvm_sequencer_launches(const kvm_sequencer* seq);
+/* Measurement support: with timing enabled every kvm_migrate call is bracketed by a
+ * pair of HIP events on the launch stream; kvm_sequencer_copy_stats waits for them and
+ * returns their summed duration, the bytes read + written by those calls and their
+ * number.  Enabling or disabling clears what was collected. */
+int kvm_sequencer_timing(kvm_sequencer* seq, int enable);
+int kvm_sequencer_copy_stats(kvm_sequencer* seq, double* ms_out, int64_t* bytes_out, int64_t* launches_out);
+
 /* ---- diagnostics ---------------------------------------------------------- */
 const char* kvm_strerror(int status);
 /* Detail of the last failure on the calling thread ("" if none); the pointer

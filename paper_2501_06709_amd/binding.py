@@ -98,6 +98,24 @@ def lib():
         L.kvm_freelist_reserve.argtypes = [VP, I32, VP]
         L.kvm_divide_moves.restype = ctypes.c_int
         L.kvm_divide_moves.argtypes = [VP, I32, VP, I32, VP, I32, I32, VP]
+        L.kvm_sequencer_table_ints.restype = I64
+        L.kvm_sequencer_table_ints.argtypes = [I32, I32, I32]
+        L.kvm_sequencer_create.restype = VP
+        L.kvm_sequencer_create.argtypes = [I32, I32, I32, VP, VP, I64, VP, I64]
+        L.kvm_sequencer_destroy.restype = None
+        L.kvm_sequencer_destroy.argtypes = [VP]
+        L.kvm_sequencer_stage.restype = ctypes.c_int
+        L.kvm_sequencer_stage.argtypes = [VP, P(kvm_pool), VP, P(kvm_pool), VP, VP, I32, I32, VP, VP, I32, VP, VP]
+        L.kvm_sequencer_flush.restype = ctypes.c_int
+        L.kvm_sequencer_flush.argtypes = [VP, VP]
+        L.kvm_sequencer_drain.restype = ctypes.c_int
+        L.kvm_sequencer_drain.argtypes = [VP, VP]
+        L.kvm_sequencer_launches.restype = I64
+        L.kvm_sequencer_launches.argtypes = [VP]
+        L.kvm_sequencer_timing.restype = ctypes.c_int
+        L.kvm_sequencer_timing.argtypes = [VP, ctypes.c_int]
+        L.kvm_sequencer_copy_stats.restype = ctypes.c_int
+        L.kvm_sequencer_copy_stats.argtypes = [VP, P(ctypes.c_double), P(I64), P(I64)]
         L.kvm_strerror.restype = ctypes.c_char_p
         L.kvm_strerror.argtypes = [ctypes.c_int]
         L.kvm_last_error.restype = ctypes.c_char_p

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvm.so")
-SOURCES = ["kvm_host.cpp", "kvm_copy.hip", "kvm_decode.hip"]
+SOURCES = ["kvm_host.cpp", "kvm_copy.hip", "kvm_decode.hip", "kvm_seq.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

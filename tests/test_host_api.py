@@ -251,3 +251,41 @@ def test_static_scratch_decode_rejects_a_plan_beyond_its_array():
         kvm.kvm_set_option("reset", 0)
     # the same argument checks as kvm_paged_decode
     assert "q_dev" in _einval(kvm.kvm_paged_decode_static, pool, batch, None, FAKE)
+
+
+def test_sequencer_host_logic_without_a_device():
+    """kvm_sequencer_*: sizes, argument checks, all-or-nothing allocation and the return
+    of destination blocks of orders that were staged but never enqueued.  Nothing is
+    flushed here, so no HIP call is made."""
+    L = kvm.lib()
+    assert L.kvm_sequencer_table_ints(10, 16, 4) == (4 + 2) * 2 * 10 * 16
+    assert L.kvm_sequencer_table_ints(0, 16, 4) == -1
+    n = L.kvm_sequencer_table_ints(10, 4, 2)
+    host = np.zeros(n, np.int32)
+    assert not L.kvm_sequencer_create(10, 4, 2, None, FAKE, n, None, 0)
+    assert not L.kvm_sequencer_create(10, 4, 2, host.ctypes.data, FAKE, n - 1, None, 0)
+    assert b"table" in L.kvm_last_error()
+    seq = L.kvm_sequencer_create(10, 4, 2, host.ctypes.data, FAKE, n, None, 0)
+    assert seq
+    src, dst = _pool(32), _pool(32, base=FAKE + (1 << 32))
+    fs, fd = kvm.FreeList(32), kvm.FreeList(32, [1, 0, 1] + [0] * 29)
+    table = np.array([3, 9, 4], np.int32)
+    fs.reserve(table)
+    out = np.full(4, -1, np.int32)
+
+    def stage(k, tab=table, q=None, o=None, row=0, n_tab=None):
+        return L.kvm_sequencer_stage(seq, ctypes.byref(src.c), fs._h, ctypes.byref(dst.c), fd._h,
+                                     tab.ctypes.data, len(tab) if n_tab is None else n_tab, k, q, o, row,
+                                     out.ctypes.data, None)
+
+    assert stage(49) == kvm.KVM_EINVAL and stage(-1) == kvm.KVM_EINVAL          # k beyond the table
+    assert stage(16, np.array([3, 32, 4], np.int32)) == kvm.KVM_EINVAL            # id outside the pool
+    assert stage(16, q=FAKE, o=None) == kvm.KVM_EINVAL                            # decode without an output
+    assert stage(16, np.arange(11, dtype=np.int32), n_tab=11) == kvm.KVM_EINVAL   # longer than max_blocks
+    assert fd.available() == 30 and (out == -1).all()
+    assert stage(40) == kvm.KVM_OK
+    assert list(out[:3]) == [1, 3, 4] and fd.available() == 27                    # lowest free ids first
+    assert stage(0) == kvm.KVM_OK and fd.available() == 27                        # a pure token-transfer order
+    assert L.kvm_sequencer_launches(seq) == 0
+    L.kvm_sequencer_destroy(seq)            # never enqueued: the destination blocks go back
+    assert fd.available() == 30 and fs.available() == 29                          # ... the source stays allocated

@@ -328,41 +328,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 
   const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head;
   const char* vbase = kbase + a.stride_kv;
-  const uint32_t lane_off = (uint32_t)row * a.stride_slot + (uint32_t)sub * 16u;
+
+  // Which part of the context a wave takes.
+  //  SLICED (head_dim 128, 16-token blocks: one load instruction covers four token
+  //  rows): wave w takes token rows 4w .. 4w+3 of EVERY block, and one step of its loop
+  //  covers four consecutive blocks, one load instruction each.  The four waves then
+  //  read every 4 KiB piece together, advance in lockstep and do exactly the same
+  //  amount of work, which is what lets a workgroup hand its slot on without one wave
+  //  trailing the others (a stream of random 4 KiB pieces read this way runs 6 % faster
+  //  than one where each wave reads whole pieces of its own, measured on MI355X with
+  //  sixteen pieces per wave).
+  //  Otherwise wave w takes whole blocks jb + w, jb + w + 4, ...
+  constexpr bool SLICED = (TPI * 4 == B);
+  constexpr int NID = SLICED ? NI : 1;   // block ids per step
+  const int nblk = je - jb;
+  const int n_it = SLICED ? (nblk + 3) / 4 : (nblk - wave + 3) / 4;  // the latter may be <= 0
+  v4u kcs[P][NI], vcs[P][NI];
+  // Block ids are uniform over the wave: they are read with scalar loads, one step
+  // ahead of their use, on the scalar cache's own path instead of queueing behind
+  // the streamed tiles.  (The table does not change while the kernel runs; reading
+  // it through the constant address space is what makes the compiler use scalar
+  // loads inside the loop, where it otherwise falls back to a vector load and a
+  // full wait.)  Indices past the range are clamped to its last entry.
+  const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + (SLICED ? 0 : wave));
+  struct Ids { int v[NID]; };
+  auto block_ids = [&](int it) {
+    Ids r;
+    if constexpr (SLICED) {
+#pragma unroll
+      for (int i = 0; i < NID; ++i) r.v[i] = tab[min(4 * it + i, nblk - 1)];
+    } else {
+      r.v[0] = tab[4 * min(it, n_it - 1)];
+    }
+    return r;
+  };
+  const uint32_t lane_off = (uint32_t)((SLICED ? 4 * wave : 0) + row) * a.stride_slot + (uint32_t)sub * 16u;
   const uint32_t inst_off = (uint32_t)TPI * a.stride_slot;
 
-  // this wave handles blocks jb + wave, jb + wave + 4, ...
-  const int n_it = (je - jb - wave + 3) / 4;  // may be <= 0
-  v4u kcs[P][NI], vcs[P][NI];
-  // Block ids are uniform over the wave: they are read with scalar loads (entry
-  // 4*it of the wave's part of the table), one block ahead of their use, on the
-  // scalar cache's own path instead of queueing behind the streamed tiles.
-  // (The table does not change while the kernel runs; reading it through the
-  // constant address space is what makes the compiler use scalar loads inside the
-  // loop, where it otherwise falls back to a vector load and a full wait.)
-  const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + wave);
-  auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };   // clamped: always one of the wave's entries
-  int id_next = 0;   // id of block it + P while block it is being consumed
-  auto load_k = [&](int blk_id, v4u* kd) {
-    const char* kp = kbase + (int64_t)blk_id * a.stride_block + lane_off;
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-      kd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(kp + i * inst_off));
-  };
-  auto load_v = [&](int blk_id, v4u* vd) {
-    const char* vp = vbase + (int64_t)blk_id * a.stride_block + lane_off;
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-      vd[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(vp + i * inst_off));
-  };
-
-  // Software pipeline with P K and P V register tiles: K of block it + P is
-  // requested as soon as the scores of block it are formed, V of block it + P as
-  // soon as the V rows of block it are accumulated, so loads are always in flight
-  // while a tile is being consumed.  Every iteration issues both
-  // tile loads unconditionally; after the last block they go to the wave's own
-  // query row (valid, aligned, cached), which keeps the loop free of the register
-  // copies a conditional load would need.
+  // Software pipeline with P K and P V register tiles: K of step it + P is
+  // requested as soon as the scores of step it are formed, V of step it + P as
+  // soon as the V rows of step it are accumulated, so loads are always in flight
+  // while a tile is being consumed.  Every step issues both tile loads
+  // unconditionally; loads that have no block to read (after the last step, or
+  // past the last block of a sliced step) go to the wave's own query row (valid,
+  // aligned, cached), which keeps the loop free of the register copies a
+  // conditional load would need.
   // s_waitcnt immediates (vmcnt in bits 3:0 and 15:14, the other counters left at
   // their maximum).  The explicit waits below keep the compiler from draining all
   // loads at the top of every iteration: without it it cannot prove that the query
@@ -370,30 +380,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   constexpr int kTileLoads = 2 * P * NI;                 // tile loads that may stay in flight (<= 63)
   constexpr int kWaitAllButTiles = 0x0F70 | (kTileLoads & 15) | ((kTileLoads >> 4) << 14);
   const char* dummy = reinterpret_cast<const char*>(
-      a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D);   // D*2 >= 128 bytes, 16-byte aligned
-  auto load_tile = [&](bool real, const char* base, int blk_id, v4u* td) {
-    const char* p = real ? base + (int64_t)blk_id * a.stride_block + lane_off : dummy + (uint32_t)sub * 16u;
-    const uint32_t step = real ? inst_off : 0u;
+      a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D) + (uint32_t)sub * 16u;   // D*2 >= 128 bytes, 16-byte aligned
+  // tile of step `it` (ids: its block ids); it >= n_it reads the dummy row
+  auto load_tile = [&](int it, const char* base, const Ids& ids, v4u* td) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i * step));
+    for (int i = 0; i < NI; ++i) {
+      const bool real = SLICED ? 4 * it + i < nblk : it < n_it;
+      const char* p = real ? base + (int64_t)ids.v[SLICED ? i : 0] * a.stride_block + lane_off + (SLICED ? 0u : i * inst_off)
+                           : dummy;
+      td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+    }
   };
-  // One block of the context.  MASKED handles a last block that is only partly
-  // context; full blocks take the mask-free instance.
-  auto step = [&](auto masked_tag, auto slot_tag, int it, int t_limit) {
+  // Context slots of the block that instruction i of step `it` reads, counted from
+  // the instruction's first token row: only the request's last block can be partly
+  // context.
+  auto token_limit = [&](int it, int i) {
+    if constexpr (SLICED) {
+      const int bi = 4 * it + i;
+      return bi < nblk ? min(B, k - (jb + bi) * B) - 4 * wave : 0;
+    } else {
+      return k - (jb + wave + 4 * it) * B - i * TPI;
+    }
+  };
+  Ids id_next = {};   // ids of step it + P while step it is being consumed
+  // One step.  MASKED handles a step that contains slots past the context; full
+  // steps take the mask-free instance.
+  auto step = [&](auto masked_tag, auto slot_tag, int it) {
     constexpr bool MASKED = decltype(masked_tag)::value;
-    constexpr int S = decltype(slot_tag)::value;   // register tile that holds block it
+    constexpr int S = decltype(slot_tag)::value;   // register tile that holds step it
     v4u(&kc)[NI] = kcs[S];
     v4u(&vc)[NI] = vcs[S];
-    const bool more = it + P < n_it;
+    int lim[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) lim[i] = MASKED ? token_limit(it, i) : TPI;
     float s[NI][G];
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int g = 0; g < G; ++g) s[i][g] = group_sum<LPT>(dot8<BF16>(qp[g], kc[i]));
     __builtin_amdgcn_sched_barrier(0);
-    const int id_after = block_id(it + P + 1);
-    load_tile(more, kbase, id_next, kc);
+    const Ids id_after = block_ids(it + P + 1);
+    load_tile(it + P, kbase, id_next, kc);
     __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -403,14 +430,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       float mx = m[g];
 #pragma unroll
       for (int i = 0; i < NI; ++i)
-        if (!MASKED || i * TPI + row < t_limit) mx = fmaxf(mx, s[i][g] * sc);
+        if (!MASKED || row < lim[i]) mx = fmaxf(mx, s[i][g] * sc);
       const float alpha = __builtin_amdgcn_exp2f(m[g] - mx);
       m[g] = mx;
       float add = 0.f;
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
         const float e = __builtin_amdgcn_exp2f(fmaf(s[i][g], sc, -mx));
-        s[i][g] = (!MASKED || i * TPI + row < t_limit) ? e : 0.f;
+        s[i][g] = (!MASKED || row < lim[i]) ? e : 0.f;
         add += s[i][g];
       }
       lsum[g] = lsum[g] * alpha + add;
@@ -422,7 +449,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       // their V rows so that a zero weight cannot turn them into NaN.
 #pragma unroll
       for (int i = 0; i < NI; ++i)
-        if (i * TPI + row >= t_limit) vc[i] = v4u{0u, 0u, 0u, 0u};
+        if (row >= lim[i]) vc[i] = v4u{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -434,42 +461,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
         for (int c = 0; c < 8; ++c) o[g][c] = fmaf(s[i][g], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    load_tile(more, vbase, id_next, vc);
+    load_tile(it + P, vbase, id_next, vc);
     id_next = id_after;
     __builtin_amdgcn_sched_barrier(0);
   };
-  // Only the request's last block can be partly context, and it is the last
-  // iteration of the one wave that owns it: all other iterations run the mask-free
-  // instance in a loop of their own.
+  // Only the request's last block can be partly context, so at most the wave's last
+  // step needs masks: all other steps run the mask-free instance in a loop of their own.
   if (n_it > 0) {
     using S0 = std::integral_constant<int, 0>;
     using S1 = std::integral_constant<int, P - 1>;
 #pragma unroll
-    for (int j = 0; j < P; ++j) {   // a wave with fewer than P blocks loads its last one twice
-      const int idj = block_id(j);
-      load_k(idj, kcs[j]);
+    for (int j = 0; j < P; ++j) {
+      const Ids idj = block_ids(j);
+      load_tile(j, kbase, idj, kcs[j]);
       __builtin_amdgcn_sched_barrier(0);
-      load_v(idj, vcs[j]);
+      load_tile(j, vbase, idj, vcs[j]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    id_next = block_id(P);
+    id_next = block_ids(P);
     __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);       // queries have arrived
-    const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;  // context slots in this wave's last block
-    const int n_main = t_last < B ? n_it - 1 : n_it;
-    if constexpr (P == 1) {
-      for (int it = 0; it < n_main; ++it) step(std::false_type{}, S0{}, it, B);
-      if (n_main < n_it) step(std::true_type{}, S0{}, n_main, t_last);
+    // steps whose slots are all context
+    int n_main;
+    if constexpr (SLICED) {
+      const int n_full = min(nblk, (k - jb * B) / B);   // full blocks of the range
+      n_main = n_full / 4;
     } else {
-      // blocks alternate between the two register tiles: even ones in tile 0
+      const int t_last = k - (jb + wave + 4 * (n_it - 1)) * B;  // context slots in this wave's last block
+      n_main = t_last < B ? n_it - 1 : n_it;
+    }
+    if constexpr (P == 1) {
+      for (int it = 0; it < n_main; ++it) step(std::false_type{}, S0{}, it);
+      if (n_main < n_it) step(std::true_type{}, S0{}, n_main);
+    } else {
+      // steps alternate between the two register tiles: even ones in tile 0
       int it = 0;
       for (; it + 1 < n_main; it += 2) {
-        step(std::false_type{}, S0{}, it, B);
-        step(std::false_type{}, S1{}, it + 1, B);
+        step(std::false_type{}, S0{}, it);
+        step(std::false_type{}, S1{}, it + 1);
       }
-      if (it < n_main) step(std::false_type{}, S0{}, it, B);
+      if (it < n_main) step(std::false_type{}, S0{}, it);
       if (n_main < n_it) {
-        if (n_main & 1) step(std::true_type{}, S1{}, n_main, t_last);
-        else step(std::true_type{}, S0{}, n_main, t_last);
+        if (n_main & 1) step(std::true_type{}, S1{}, n_main);
+        else step(std::true_type{}, S0{}, n_main);
       }
     }
   }
@@ -477,24 +510,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, s_ws);
 }
 
-// Grouped-query decode with the scores on the matrix cores (group of four query
-// heads, head_dim 128, 16-token blocks).  q.K^T of one block is a 16 x 4 x 128
-// contraction: four v_mfma_f32_16x16x32 with the K tile as the A operand (rows =
-// tokens) and the four query heads in the first four columns of the B operand
-// replace 64 dot instructions and 64 cross-lane additions of the vector version.
-// Lane layouts (checked on the device against a plain matrix product):
-//   A: lane x holds row x%16, k = 8*(x/16) .. +7      -> K[token x%16][32j + 8*(x/16) ..]
-//   B: lane x holds column x%16, k = 8*(x/16) .. +7   -> Q[head x%16][32j + 8*(x/16) ..]
-//   D: lane x holds rows 4*(x/16) .. +3 of column x%16 -> score[token 4*(x/16)+r][head x%16]
-// so lane (head, lane row) owns the scores of four consecutive tokens and keeps the
-// online-softmax state of that (head, lane row) pair.  The V tile is loaded so
-// that lane row `row` holds tokens 4*row .. 4*row+3 as well, 16 bytes of each per
-// lane; the four weights and the rescale factor of every head then travel from
-// lane (head, row) to the sixteen lanes of the row with ds_bpermute (no LDS memory
-// is touched) and P.V stays on the vector unit.  K is read in 64-byte pieces per
-// token and instruction (two instructions complete each 128-byte line).
-// WMAX as for decode_kernel (8B workload: 6.27 TB/s at two waves per SIMD, 6.08 at
-// three, 5.87 at four).
+// Grouped-query decode with the scores on the matrix cores (groups of four or
+// eight query heads, head_dim 128, 16-token blocks).  q.K^T of one block is a
+// 16 x G x 128 contraction: four v_mfma_f32_16x16x32 with K as the A operand and
+// the query heads as columns of the B operand replace 64 dot instructions and 64
+// cross-lane additions of the vector version.
+// Operand layouts of the instruction (checked on the device against a plain
+// matrix product): A: lane x holds row x%16, k = 8*(x/16) .. +7; B: lane x holds
+// column x%16, k = 8*(x/16) .. +7; D: lane x holds rows 4*(x/16) .. +3 of column x%16.
+// Taking the sixteen rows as the block's sixteen tokens would make each load
+// instruction read 64 bytes of every token, two instructions per 128-byte line,
+// and a share of those lines is then fetched from HBM twice (measured: 3 % more
+// bytes than the cache holds tokens).  Instead one instruction reads whole lines:
+// rows 0..7 are eight tokens with the first half of a line as their k range, rows
+// 8..15 the same eight tokens with the second half; the query heads occupy 2G
+// columns, G with the dims of the first half and G with those of the second.  The
+// result tile then holds the two partial scores of (token, head) in two lanes (and
+// cross products nobody reads); one ds_bpermute per score adds them.  MFMA i
+// covers tokens 8*(i/2) .. +7 and line i%2; for the second eight tokens the halves
+// are swapped so that lane (head, lane row g) ends up owning the scores of tokens
+// 4g .. 4g+3 of the block and keeps the online-softmax state of that pair.  The V
+// tile is loaded so that lane row g holds tokens 4g .. 4g+3 as well, 16 bytes of
+// each per lane; the four weights and the rescale factor of every head then travel
+// from lane (head, g) to the sixteen lanes of the row with ds_bpermute (no LDS
+// memory is touched) and P.V stays on the vector unit.
+// WMAX as for decode_kernel.
 template <int D, int B, int G, bool BF16, int WMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma_kernel(const DecArgs a) {
   static_assert(D == 128 && B == 16 && (G == 4 || G == 8), "shape of the matrix-core variant");
@@ -514,13 +554,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   if (threadIdx.x == 0) s_ws.done = 0u;
   __syncthreads();
 
-  // B operand: dims 32j + 8*row .. +7 of head `sub`; columns >= G are zero
+  // B operand of line ln (dims 64*ln .. 64*ln+63): column c < 2G holds head c % G,
+  // dims 64*ln + 32*(c / G) + 8*row .. +7; columns >= 2G are zero
   const uint16_t* qrow = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D;
-  v4u qb[4];
+  v4u qb[2];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    qb[j] = v4u{0u, 0u, 0u, 0u};
-    if (sub < G) qb[j] = *reinterpret_cast<const v4u*>(qrow + sub * D + 32 * j + 8 * row);
+  for (int ln = 0; ln < 2; ++ln) {
+    qb[ln] = v4u{0u, 0u, 0u, 0u};
+    if (sub < 2 * G) qb[ln] = *reinterpret_cast<const v4u*>(qrow + (sub % G) * D + 64 * ln + 32 * (sub / G) + 8 * row);
   }
   const float sc = a.scale_log2e;
 
@@ -533,10 +574,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 
   const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head;
   const char* vbase = kbase + a.stride_kv;
-  const uint32_t k_off = (uint32_t)sub * a.stride_slot + (uint32_t)row * 16u;       // + 64*j
+  // A operand of MFMA i: tokens 8*(i/2) .. +7 of the block, line i%2 of their rows;
+  // lane row-halves carry the two 64-byte halves of the line (swapped for i >= 2)
+  const uint32_t k_off_a = (uint32_t)(sub % 8) * a.stride_slot + (uint32_t)(sub / 8) * 64u + (uint32_t)row * 16u;
+  const uint32_t k_off_b = (uint32_t)(8 + sub % 8) * a.stride_slot + (uint32_t)(1 - sub / 8) * 64u + (uint32_t)row * 16u;
   const uint32_t v_off = (uint32_t)(4 * row) * a.stride_slot + (uint32_t)sub * 16u;  // + i*stride_slot
   const char* dummy = reinterpret_cast<const char*>(qrow) + (uint32_t)sub * 16u;     // 256 valid bytes
   const int bp_row = 16 * row * 4;  // ds_bpermute byte address of lane (head 0, this lane's row)
+  const int bp_pair = ((lane ^ 32) + G) * 4;   // lane that holds the other half-line's partial scores
+  const bool low_rows = row < 2;
 
   const int n_it = (je - jb - wave + 3) / 4;
   v4u kcs[P][4], vcs[P][4];
@@ -545,11 +591,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   auto block_id = [&](int it) { return tab[4 * min(it, n_it - 1)]; };
   int id_next = 0;
   auto load_k = [&](bool real, int blk_id, v4u* kc) {
-    const char* p = real ? kbase + (int64_t)blk_id * a.stride_block + k_off : dummy;
-    const uint32_t stp = real ? 64u : 0u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      kc[j] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + j * stp));
+    const char* pa = real ? kbase + (int64_t)blk_id * a.stride_block + k_off_a : dummy;
+    const char* pb = real ? kbase + (int64_t)blk_id * a.stride_block + k_off_b : dummy;
+    const uint32_t stp = real ? 128u : 0u;
+    kc[0] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(pa));
+    kc[1] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(pa + stp));
+    kc[2] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(pb));
+    kc[3] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(pb + stp));
   };
   auto load_v = [&](bool real, int blk_id, v4u* vc) {
     const char* p = real ? vbase + (int64_t)blk_id * a.stride_block + v_off : dummy;
@@ -567,18 +615,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
     v4u(&kc)[4] = kcs[S];
     v4u(&vc)[4] = vcs[S];
     const bool more = it + P < n_it;
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    v4f half[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // partial scores of tokens 0..7 and 8..15
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int i = 0; i < 4; ++i) {
       if (BF16) {
         typedef __bf16 b8 __attribute__((ext_vector_type(8)));
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, kc[j]), __builtin_bit_cast(b8, qb[j]),
-                                                      acc, 0, 0, 0);
+        half[i / 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, kc[i]),
+                                                              __builtin_bit_cast(b8, qb[i % 2]), half[i / 2], 0, 0, 0);
       } else {
         typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kc[j]), __builtin_bit_cast(h8, qb[j]),
-                                                     acc, 0, 0, 0);
+        half[i / 2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kc[i]),
+                                                             __builtin_bit_cast(h8, qb[i % 2]), half[i / 2], 0, 0, 0);
       }
+    }
+    // Lane (column c, row g) holds rows 4g .. 4g+3 of column c.  The products that
+    // pair a half-line with the query dims of the same half sit, for tokens 0..7, in
+    // (c < G, g < 2) and (G <= c < 2G, g >= 2), and for tokens 8..15 (halves swapped)
+    // in (c < G, g >= 2) and (G <= c < 2G, g < 2): lane (head, g) adds its own part
+    // and the part of lane (head + G, g ^ 2), which makes it the owner of tokens
+    // 4g .. 4g+3 of the block.
+    v4f acc;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float own = low_rows ? half[0][t] : half[1][t];
+      const float give = low_rows ? half[1][t] : half[0][t];
+      acc[t] = own + __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_pair, __builtin_bit_cast(int, give)));
     }
     __builtin_amdgcn_sched_barrier(0);
     const int id_after = block_id(it + P + 1);

@@ -362,12 +362,12 @@ const char* kvm_last_error(void);
  *                       instead of by pool block; -1 (default): kvm_pack does when
  *                       the batch's mean request moves 4096 tokens or more.
  *  "decode.mfma"        scores on the matrix cores (head_dim 128, 16-token blocks):
- *                       -1 (default): groups of eight query heads always, groups of
- *                       four when the mean context per workgroup is below 256
- *                       blocks; 0 never; 1 for groups of four and eight always.
+ *                       -1 (default) and 1: groups of four and of eight query
+ *                       heads; 0 never.
  *  "decode.cap_waves"   -1 (default): the tuned decode kernels run at most two waves
  *                       per SIMD, with two tiles in flight, when the mean context per
- *                       workgroup is 12 blocks or more; 0 never, 1 always.
+ *                       workgroup is 12 blocks or more (the matrix-core kernel for
+ *                       groups of four never does); 0 never, 1 always.
  *  "decode.split_target" workgroups a decode launch should reach by splitting
  *                       contexts (default 2048).
  *  "decode.max_splits"  1..64 (default 16).

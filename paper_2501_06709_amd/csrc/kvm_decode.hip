@@ -737,6 +737,216 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, mg, lg, o, s_ws);
 }
 
+// Groups of four query heads, scores on the matrix cores, waves sliced by token row
+// as in decode_kernel: wave w takes token rows 4w .. 4w+3 of every block and one step
+// covers four consecutive blocks.  One v_mfma_f32_16x16x32 then handles the four token
+// rows a wave owns in one block, over all 128 dims and all four heads, from ONE load
+// instruction that reads the rows' 1 KiB as a contiguous run:
+//   lane x = 16g + 4t + p loads the 16 bytes (8 dims) number 4g + p of token row t.
+//   As the A operand (row x%16 = 4t + p, k = 8g .. 8g+7) this is a matrix whose row
+//   (t, p) holds, of token t, the dims of chunk set p = {p, 4+p, 8+p, 12+p}.
+//   The B operand holds in column 4h + p', k = 8g .. 8g+7, the dims of chunk 4g + p'
+//   of head h's query: chunk set p' of head h.
+//   Element ((t, p), (h, p')) of the product is the partial score of token t and head
+//   h over chunk set p when p = p' (a cross product nobody reads otherwise); the
+//   sixteen dims chunks are covered by p = 0..3, so the score is the sum of the four
+//   diagonal elements.  Lane x of the result holds rows 4(x/16) .. +3 of column x%16,
+//   i.e. token row x/16, chunk sets 0..3 in its four registers, for head (x%16)/4 and
+//   p' = x%4: register x%4 is the useful one, and the four lanes of a quad add up
+//   to the score (four quad-broadcast DPP operations).
+// Every lane of quad (token row r, head h) then keeps the online-softmax state of
+// that pair; the V rows are loaded one token row per lane row (1 KiB contiguous per
+// instruction as well), the weights travel from lane (r, 4h) to the sixteen lanes of
+// the row with ds_bpermute and P.V stays on the vector unit.
+template <int D, int B, bool BF16, int WMAX>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma4_kernel(const DecArgs a) {
+  static_assert(D == 128 && B == 16, "shape of the matrix-core variant");
+  constexpr int G = 4;
+  constexpr int P = WMAX == 2 ? 2 : 1;   // tiles in flight per wave and per K / V (as in decode_kernel)
+  __shared__ WaveStates<D, G> s_ws;
+
+  const WorkItem wi = work_item<B, G>(a);
+  if (wi.jb >= wi.je) return;  // empty context or an empty split: uniform over the workgroup
+  const DecReq rq = wi.rq;
+  const int h = wi.h, l = wi.l, split = wi.split, k = rq.k, jb = wi.jb, je = wi.je;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sub = lane % 16;
+  const int row = lane / 16;
+  const int hq0 = wi.hq0;
+  if (threadIdx.x == 0) s_ws.done = 0u;
+  __syncthreads();
+
+  // B operand: column sub = 4h + p', k slice `row`: dims 8 * (4 * row + p') .. +7 of head h
+  const uint16_t* qrow = a.q + (((int64_t)rq.row * a.L + l) * a.Hq + hq0) * D;
+  const v4u qb = *reinterpret_cast<const v4u*>(qrow + (sub / 4) * D + 8 * (4 * row + sub % 4));
+  const float sc = a.scale_log2e;
+
+  float m = kNegBig, lsum = 0.f;  // state of (head sub / 4, token row `row`), equal over the quad
+  float o[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] = 0.f;
+
+  const char* kbase = a.base + (int64_t)l * a.stride_layer + (int64_t)h * a.stride_head;
+  const char* vbase = kbase + a.stride_kv;
+  const uint32_t k_off = (uint32_t)(4 * wave + sub / 4) * a.stride_slot + (uint32_t)(4 * row + sub % 4) * 16u;
+  const uint32_t v_off = (uint32_t)(4 * wave + row) * a.stride_slot + (uint32_t)sub * 16u;
+  const char* dummy = reinterpret_cast<const char*>(qrow) + (uint32_t)sub * 16u;     // 256 valid bytes
+  const int bp_row = 16 * row * 4;  // ds_bpermute byte address of lane (token row `row`, column 0)
+
+  const int nblk = je - jb;
+  const int n_it = (nblk + 3) / 4;
+  v4u kcs[P][4], vcs[P][4];
+  const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb);
+  struct Ids { int v[4]; };
+  auto block_ids = [&](int it) {
+    Ids r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.v[i] = tab[min(4 * it + i, nblk - 1)];
+    return r;
+  };
+  // tile of step `it`: instruction i reads the wave's rows of block 4*it + i, or the
+  // query row (valid, cached) where the range has no such block
+  auto load_tile = [&](int it, const char* base, uint32_t off, const Ids& ids, v4u* td) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const char* p = 4 * it + i < nblk ? base + (int64_t)ids.v[i] * a.stride_block + off : dummy;
+      td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+    }
+  };
+  constexpr int kTileLoads = 8 * P;
+  constexpr int kWaitAllButTiles = 0x0F70 | (kTileLoads & 15) | ((kTileLoads >> 4) << 14);
+  Ids id_next = {};
+
+  auto step = [&](auto masked_tag, auto slot_tag, int it) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    constexpr int S = decltype(slot_tag)::value;   // register tile that holds step it
+    v4u(&kc)[4] = kcs[S];
+    v4u(&vc)[4] = vcs[S];
+    // context rows of block 4*it + i, counted from this wave's first row
+    int lim[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int bi = 4 * it + i;
+      lim[i] = !MASKED ? 4 : (bi < nblk ? min(B, k - (jb + bi) * B) - 4 * wave : 0);
+    }
+    float s[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v4f d = {0.f, 0.f, 0.f, 0.f};
+      if (BF16) {
+        typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+        d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(b8, kc[i]), __builtin_bit_cast(b8, qb), d, 0, 0, 0);
+      } else {
+        typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kc[i]), __builtin_bit_cast(h8, qb), d, 0, 0, 0);
+      }
+      // lane p' of the quad contributes its register p'
+      auto bcast = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value, 0xF, 0xF, true));
+      };
+      s[i] = bcast(d[0], std::integral_constant<int, 0x00>{}) + bcast(d[1], std::integral_constant<int, 0x55>{}) +
+             bcast(d[2], std::integral_constant<int, 0xAA>{}) + bcast(d[3], std::integral_constant<int, 0xFF>{});
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const Ids id_after = block_ids(it + P + 1);
+    load_tile(it + P, kbase, k_off, id_next, kc);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // online softmax of (head sub / 4, token row `row`) over the step's four blocks
+    float mx = m;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (!MASKED || row < lim[i]) mx = fmaxf(mx, s[i] * sc);
+    const float alpha = __builtin_amdgcn_exp2f(m - mx);
+    m = mx;
+    float p[4], add = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float e = __builtin_amdgcn_exp2f(fmaf(s[i], sc, -mx));
+      p[i] = (!MASKED || row < lim[i]) ? e : 0.f;
+      add += p[i];
+    }
+    lsum = lsum * alpha + add;
+    // weights and rescale factor of head g: from lane (row, 4g) to the whole lane row
+    float pw[G][4], al[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      al[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, alpha)));
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        pw[g][i] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, p[i])));
+    }
+    if (MASKED) {
+      // rows past the context may hold anything: clear them so that a zero weight
+      // cannot turn a NaN pattern into NaN
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (row >= lim[i]) vc[i] = v4u{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] *= al[g];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float vf[8];
+      widen8<BF16>(vc[i], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[g][i], vf[c], o[g][c]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_tile(it + P, vbase, v_off, id_next, vc);
+    id_next = id_after;
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  {
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, P - 1>;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      const Ids idj = block_ids(j);
+      load_tile(j, kbase, k_off, idj, kcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_tile(j, vbase, v_off, idj, vcs[j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    id_next = block_ids(P);
+    __builtin_amdgcn_s_waitcnt(kWaitAllButTiles);  // queries have arrived
+    const int n_full = min(nblk, (k - jb * B) / B);   // full blocks of the range
+    const int n_main = n_full / 4;                    // steps whose rows are all context
+    if constexpr (P == 1) {
+      for (int it = 0; it < n_main; ++it) step(std::false_type{}, S0{}, it);
+      if (n_main < n_it) step(std::true_type{}, S0{}, n_main);
+    } else {
+      int it = 0;
+      for (; it + 1 < n_main; it += 2) {
+        step(std::false_type{}, S0{}, it);
+        step(std::false_type{}, S1{}, it + 1);
+      }
+      if (it < n_main) step(std::false_type{}, S0{}, it);
+      if (n_main < n_it) {
+        if (n_main & 1) step(std::true_type{}, S1{}, n_main);
+        else step(std::true_type{}, S0{}, n_main);
+      }
+    }
+  }
+
+  // the state of head g sits in the lanes of quad (row, g): hand it to all lanes of the row
+  float mg[G], lg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, m)));
+    lg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, lsum)));
+  }
+  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, mg, lg, o, s_ws);
+}
+
 // Log-sum-exp merge of the context splits, in split order.
 template <int D, int B, bool BF16>
 __global__ __launch_bounds__(D) void merge_kernel(const DecArgs a) {
@@ -867,7 +1077,7 @@ static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, 
       return;
     }
     if (p.mfma && p.g_tile == 4) {
-      hipLaunchKernelGGL((decode_mfma_kernel<D, B, 4, BF16, WMAX>), grid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((decode_mfma4_kernel<D, B, BF16, WMAX>), grid, dim3(256), 0, st, a);
       return;
     }
   }
@@ -995,22 +1205,21 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const int32_
     // Which instance runs, by group width and mean context per workgroup (measured
     // on MI355X with equal-length batches, GB/s of KV read; "capped" = at most two
     // waves per SIMD, which also leaves the registers for two tiles in flight):
-    //  - capped beats uncapped from 16 blocks per workgroup on, for every group width
-    //    (one head per KV head, 32 blocks: 6450 against 6310; groups of four, 64
-    //    blocks: 6240 against 5840); only very short contexts (8 blocks) prefer more
-    //    waves (6290 against 5290);
-    //  - groups of four: scores on the matrix cores win up to 128 blocks (32 blocks:
-    //    6120 against 5885, 128: 6300 against 6190), the vector kernel wins on long
-    //    contexts (2048 blocks: 6630 against 6420).
+    //  - vector kernel, one head per KV head: capped wins from 16 blocks per workgroup
+    //    on (32 blocks: 6640 against 6370, 128: 6600 against 6470), uncapped below
+    //    (8 blocks: 6280 against 5660, 4 blocks: 5970 against 4110);
+    //  - groups of four and of eight run with the scores on the matrix cores at every
+    //    length (groups of four, 60 blocks: 6220 against 5370 for the vector kernel,
+    //    2048 blocks: 6280 against 6150); the kernel for groups of four is never capped
+    //    (16 blocks: 5920 against 5730, 128 blocks: 6320 against 6260).
     // "decode.cap_waves" (0 never, 1 always) and "decode.mfma" (0 never, 1 always)
     // override.
     int64_t live = 0;
     for (int r = 0; r < v.n_req; ++r) live += v.nb[r] > 0;
     const int64_t mean_blocks = v.total_blocks / std::max<int64_t>(1, live * p.n_splits);
     const int cap_mode = options().decode_cap_waves, mfma_mode = options().decode_mfma;
-    p.cap = cap_mode < 0 ? mean_blocks >= 12 : cap_mode != 0;
-    p.mfma = l.head_dim == 128 && l.block_tokens == 16 &&
-             (p.g_tile == 8 ? mfma_mode != 0 : p.g_tile == 4 && (mfma_mode < 0 ? mean_blocks < 256 : mfma_mode != 0));
+    p.mfma = l.head_dim == 128 && l.block_tokens == 16 && (p.g_tile == 8 || p.g_tile == 4) && mfma_mode != 0;
+    p.cap = cap_mode < 0 ? (mean_blocks >= 12 && !(p.mfma && p.g_tile == 4)) : cap_mode != 0;
   }
 
   DecArgs a;

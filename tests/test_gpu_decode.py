@@ -75,6 +75,30 @@ def test_decode_matches_oracle(oracle, m, variant):
     assert np.abs(got - ref).max() < TOL, np.abs(got - ref).max()
 
 
+@pytest.mark.parametrize("variant", ["matrix_core_scores", "vector_unit_scores"])
+@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2]], ids=["mha128", "gqa4"])
+def test_every_context_length_up_to_nine_blocks(oracle, m, variant):
+    """The kernels for head_dim 128 give each wave four token rows of every block and
+    walk four blocks per step: every number of blocks modulo four and every fill of the
+    last block must come out right, in both the capped and the uncapped instance."""
+    lens = list(range(1, 9 * 16 + 2))
+    n_blocks = sum(-(-k // 16) for k in lens)
+    src, _ = make_pair(m, n_blocks + 8, 8, lens, [0] * len(lens), seed=31, finite=True)
+    side = Side(m, n_blocks + 8, src.host, src.tables, lens)
+    q = wl.gen_q(31, m, len(lens))
+    ref = oracle_decode(oracle, side, q)
+    try:
+        set_variant(variant)
+        for cap in (0, 1):
+            kvm.kvm_set_option("decode.cap_waves", cap)
+            got = gpu_decode(side, q)
+            err = np.abs(got - ref).reshape(len(lens), -1).max(axis=1)
+            assert err.max() < TOL, (cap, int(err.argmax()) + 1, err.max())
+    finally:
+        kvm.kvm_set_option("decode.cap_waves", -1)
+        set_variant("shipped")
+
+
 def test_decode_k0_rows_untouched_and_scale(oracle):
     m = wl.Model("z", 2, 2, 4, 128, 16, "bf16")
     lens = [40, 20, 9]

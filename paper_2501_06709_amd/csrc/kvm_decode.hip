@@ -202,24 +202,35 @@ struct WaveStates {
   unsigned int done;   // waves that have written their state; zeroed at workgroup start
 };
 
+// head_of[g]: the head (0 .. G-1) whose state this lane keeps in slot g; the same for
+// lanes that differ only in the token row, so that rows merge slot by slot.
 template <int D, int G, bool BF16>
 __device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq& rq, int l, int hq0, int split,
                                                  int wave, int lane, float (&m)[G], float (&lsum)[G],
-                                                 float (&o)[G][8], WaveStates<D, G>& ws) {
+                                                 float (&o)[G][8], WaveStates<D, G>& ws, const int (&head_of)[G]) {
   constexpr int LPT = D / 8;
   const int sub = lane % LPT;
-  // 1. merge the token rows of the wave
+  // 1. merge the token rows of the wave: first the maximum over the rows, then every
+  // row rescales its own state once and the rows are added up (all shuffles of a round
+  // are independent, so a round costs one cross-lane latency, not one per value)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mx = m[g];
+#pragma unroll
+    for (int x = LPT; x < 64; x <<= 1) mx = fmaxf(mx, __shfl_xor(mx, x));
+    const float w = __builtin_amdgcn_exp2f(m[g] - mx);
+    m[g] = mx;
+    lsum[g] *= w;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] *= w;
+  }
 #pragma unroll
   for (int x = LPT; x < 64; x <<= 1) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float m2 = __shfl_xor(m[g], x);
-      const float mx = fmaxf(m[g], m2);
-      const float w1 = __builtin_amdgcn_exp2f(m[g] - mx), w2 = __builtin_amdgcn_exp2f(m2 - mx);
-      lsum[g] = fmaf(__shfl_xor(lsum[g], x), w2, lsum[g] * w1);
+      lsum[g] += __shfl_xor(lsum[g], x);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) o[g][c] = fmaf(__shfl_xor(o[g][c], x), w2, o[g][c] * w1);
-      m[g] = mx;
+      for (int c = 0; c < 8; ++c) o[g][c] += __shfl_xor(o[g][c], x);
     }
   }
   // 2. row 0 holds the wave's state
@@ -227,10 +238,10 @@ __device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq&
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       if (lane == 0) {
-        ws.m[wave][g] = m[g];
-        ws.l[wave][g] = lsum[g];
+        ws.m[wave][head_of[g]] = m[g];
+        ws.l[wave][head_of[g]] = lsum[g];
       }
-      v4f* dst = reinterpret_cast<v4f*>(&ws.o[wave][g][sub * 8]);
+      v4f* dst = reinterpret_cast<v4f*>(&ws.o[wave][head_of[g]][sub * 8]);
       dst[0] = v4f{o[g][0], o[g][1], o[g][2], o[g][3]};
       dst[1] = v4f{o[g][4], o[g][5], o[g][6], o[g][7]};
     }
@@ -239,36 +250,65 @@ __device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq&
   if (lane == 0)  // release: this wave's LDS writes precede the count; acquire: the last wave sees all
     before = __hip_atomic_fetch_add(&ws.done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
   if (__builtin_amdgcn_readfirstlane(before) != 3u) return;
-  // 3. the last wave combines the four wave states, in wave order
-  for (int idx = lane; idx < G * D; idx += 64) {
-    const int g = idx / D, d = idx % D;
-    float mx = kNegBig;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) mx = fmaxf(mx, ws.m[w][g]);
-    float acc = 0.f, den = 0.f;
+  // 3. the last wave combines the four wave states, in wave order: a lane takes eight
+  // consecutive dims of one head (G * D / 8 such pieces over the 64 lanes)
+  for (int piece = lane; piece < G * LPT; piece += 64) {
+    const int g = piece / LPT, d0 = (piece % LPT) * 8;
+    float mw[4], mx = kNegBig;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float wgt = __builtin_amdgcn_exp2f(ws.m[w][g] - mx);
-      acc = fmaf(ws.o[w][g][d], wgt, acc);
+      mw[w] = ws.m[w][g];
+      mx = fmaxf(mx, mw[w]);
+    }
+    float acc[8], den = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(mw[w] - mx);
       den = fmaf(ws.l[w][g], wgt, den);
+      const v4f* src = reinterpret_cast<const v4f*>(&ws.o[w][g][d0]);
+      const v4f lo = src[0], hi = src[1];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        acc[c] = fmaf(lo[c], wgt, acc[c]);
+        acc[4 + c] = fmaf(hi[c], wgt, acc[4 + c]);
+      }
     }
     const int hq = hq0 + g;
     if (a.n_splits == 1) {
-      const float res = acc / den;
-      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d;
-      if (a.out_f32)
-        reinterpret_cast<float*>(a.out)[oi] = res;
-      else
-        reinterpret_cast<uint16_t*>(a.out)[oi] = narrow<BF16>(res);
+      const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d0;
+      // (out is only required to be 4-byte aligned: dword stores)
+      if (a.out_f32) {
+        float* dst = reinterpret_cast<float*>(a.out) + oi;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) dst[c] = acc[c] / den;
+      } else {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.out) + oi);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          dst[c] = (uint32_t)narrow<BF16>(acc[2 * c] / den) | ((uint32_t)narrow<BF16>(acc[2 * c + 1] / den) << 16);
+      }
     } else {
       float* e = ws_entry(a.ws, a, rq.slot, l, hq, split, D);
-      e[d] = acc;
-      if (d == 0) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) e[d0 + c] = acc[c];
+      if (d0 == 0) {
         e[D] = mx;
         e[D + 1] = den;
       }
     }
   }
+}
+
+template <int D, int G, bool BF16>
+__device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq& rq, int l, int hq0, int split,
+                                                 int wave, int lane, float (&m)[G], float (&lsum)[G],
+                                                 float (&o)[G][8], WaveStates<D, G>& ws) {
+  int head_of[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) head_of[g] = g;
+  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, ws, head_of);
 }
 
 // WMAX caps the waves per SIMD.  With long contexts the rate falls as more
@@ -756,13 +796,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
 //   to the score (four quad-broadcast DPP operations).
 // Every lane of quad (token row r, head h) then keeps the online-softmax state of
 // that pair; the V rows are loaded one token row per lane row (1 KiB contiguous per
-// instruction as well), the weights travel from lane (r, 4h) to the sixteen lanes of
-// the row with ds_bpermute and P.V stays on the vector unit.
+// instruction as well) and P.V stays on the vector unit.  A lane needs the weights
+// of all four heads for its token row: they come from the other quads of its lane
+// row by DPP row rotations (no LDS round trip), which makes output slot j of a lane
+// belong to the head of the quad j places to its left; the end of the kernel sorts
+// the slots back by head.
 template <int D, int B, bool BF16, int WMAX>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_mfma4_kernel(const DecArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WMAX <= 3 ? 1 : 4, WMAX))) void decode_mfma4_kernel(const DecArgs a) {
   static_assert(D == 128 && B == 16, "shape of the matrix-core variant");
   constexpr int G = 4;
-  constexpr int P = WMAX == 2 ? 2 : 1;   // tiles in flight per wave and per K / V (as in decode_kernel)
+  // Two instances: four waves per SIMD (at most 128 registers) with one tile in flight
+  // per wave and per K / V, or three waves per SIMD with two.
+  constexpr int P = WMAX <= 3 ? 2 : 1;
   __shared__ WaveStates<D, G> s_ws;
 
   const WorkItem wi = work_item<B, G>(a);
@@ -795,7 +840,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   const uint32_t k_off = (uint32_t)(4 * wave + sub / 4) * a.stride_slot + (uint32_t)(4 * row + sub % 4) * 16u;
   const uint32_t v_off = (uint32_t)(4 * wave + row) * a.stride_slot + (uint32_t)sub * 16u;
   const char* dummy = reinterpret_cast<const char*>(qrow) + (uint32_t)sub * 16u;     // 256 valid bytes
-  const int bp_row = 16 * row * 4;  // ds_bpermute byte address of lane (token row `row`, column 0)
+  // Slot j of this lane's output state belongs to the head of the quad j places to the
+  // left in the lane row (cyclically): the weights of that head reach the lane through
+  // a rotation of the row by 4j lanes (DPP, no LDS round trip), and so does the head's
+  // number, which is what tells the end of the kernel where slot j goes.
+  auto rot = [](float v, auto quads) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + 4 * decltype(quads)::value, 0xF, 0xF, true));
+  };
+  using Q1 = std::integral_constant<int, 1>;
+  using Q2 = std::integral_constant<int, 2>;
+  using Q3 = std::integral_constant<int, 3>;
+  auto rot4 = [&](float v, float (&out)[4]) {
+    out[0] = v;
+    out[1] = rot(v, Q1{});
+    out[2] = rot(v, Q2{});
+    out[3] = rot(v, Q3{});
+  };
 
   const int nblk = je - jb;
   const int n_it = (nblk + 3) / 4;
@@ -871,14 +931,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
       add += p[i];
     }
     lsum = lsum * alpha + add;
-    // weights and rescale factor of head g: from lane (row, 4g) to the whole lane row
-    float pw[G][4], al[G];
+    // weights of the four heads for this lane's token row: slot j from the quad j to the left
+    float pw[4][G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      al[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, alpha)));
+    for (int i = 0; i < 4; ++i) rot4(p[i], pw[i]);
+    // the accumulators only need rescaling when some running maximum of the wave moved
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+      float al[G];
+      rot4(alpha, al);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        pw[g][i] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, p[i])));
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[g][c] *= al[g];
     }
     if (MASKED) {
       // rows past the context may hold anything: clear them so that a zero weight
@@ -888,17 +952,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
         if (row >= lim[i]) vc[i] = v4u{0u, 0u, 0u, 0u};
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-      for (int c = 0; c < 8; ++c) o[g][c] *= al[g];
-#pragma unroll
     for (int i = 0; i < 4; ++i) {
       float vf[8];
       widen8<BF16>(vc[i], vf);
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[g][i], vf[c], o[g][c]);
+        for (int c = 0; c < 8; ++c) o[g][c] = fmaf(pw[i][g], vf[c], o[g][c]);
     }
     __builtin_amdgcn_sched_barrier(0);
     load_tile(it + P, vbase, v_off, id_next, vc);
@@ -937,14 +997,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
     }
   }
 
-  // the state of head g sits in the lanes of quad (row, g): hand it to all lanes of the row
-  float mg[G], lg[G];
+  // running maximum, sum and head number of every slot, by the same rotations
+  float mg[G], lg[G], hf[G];
+  rot4(m, mg);
+  rot4(lsum, lg);
+  rot4((float)(sub / 4), hf);
+  int head_of[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    mg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, m)));
-    lg[g] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(bp_row + 16 * g, __builtin_bit_cast(int, lsum)));
-  }
-  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, mg, lg, o, s_ws);
+  for (int g = 0; g < G; ++g) head_of[g] = (int)hf[g];
+  finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, mg, lg, o, s_ws, head_of);
 }
 
 // Log-sum-exp merge of the context splits, in split order.
@@ -1077,7 +1138,7 @@ static void launch_main(const DecArgs& a, const DecodePlan& p, const dim3 grid, 
       return;
     }
     if (p.mfma && p.g_tile == 4) {
-      hipLaunchKernelGGL((decode_mfma4_kernel<D, B, BF16, WMAX>), grid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((decode_mfma4_kernel<D, B, BF16, (WMAX == 2 ? 3 : 8)>), grid, dim3(256), 0, st, a);
       return;
     }
   }

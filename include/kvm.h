@@ -368,6 +368,10 @@ const char* kvm_last_error(void);
  *                       per SIMD, with two tiles in flight, when the mean context per
  *                       workgroup is 12 blocks or more (the matrix-core kernel for
  *                       groups of four never does); 0 never, 1 always.
+ *  "decode.spread"      log2 of the distance, in block-table entries, between the
+ *                       four blocks the head_dim-128 decode kernels read in one step
+ *                       (0..6; 0 = neighbouring entries); -1 (default): about 1 MiB of
+ *                       pool memory when ids are consecutive.
  *  "decode.split_target" workgroups a decode launch should reach by splitting
  *                       contexts (default 2048).
  *  "decode.max_splits"  1..64 (default 16).

@@ -67,6 +67,7 @@ struct DecArgs {
   int32_t n_splits;
   int32_t out_f32;
   float scale_log2e;    // softmax scale * log2(e): scores live in the exp2 domain
+  int32_t spread_log2;  // sliced kernels: log2 of the table-entry distance between the four blocks of a step
   DecReq req[kMaxReqPerLaunch];
 };
 
@@ -178,6 +179,34 @@ __device__ __forceinline__ WorkItem work_item(const DecArgs& a) {
   w.jb = w.split * per;
   w.je = min(nb, w.jb + per);
   return w;
+}
+
+// Which four blocks a step of the sliced kernels reads.  Reading four blocks that are
+// neighbours in memory with one burst of loads is the slowest way to read them: a
+// stream of 4 KiB pieces fetched four at a time runs at 6.23 TB/s when the four lie
+// 32 .. 160 KiB apart, at 6.50 when they lie 0.5 .. 1 MiB apart (or are one 16 KiB run),
+// at 6.0 when 4 .. 8 MiB apart (measured on MI355X; consecutive block ids, which a
+// lowest-id-first allocator hands out on a fresh pool, put the blocks of a request
+// exactly one block run apart).  So the table entries of a range are taken in an
+// interleaved order: while at least 4e entries remain, step o of such a group reads
+// entries o, o + e, o + 2e, o + 3e of the group (e = 2^spread_log2 entries, about
+// 1 MiB in consecutive ids); the remainder repeats this with e/2, e/4, ..., and the
+// last entries (fewer than 8) go in table order, so that the block that may be partly
+// context is still the very last position.  Returns the entry of instruction 0 of
+// step `it` and the distance e_out to the entries of instructions 1..3.  Uniform
+// over the wave, shifts and compares only: it runs on the scalar unit.
+__device__ __forceinline__ int step_first_entry(int it, int nblk, int spread_log2, int& e_out) {
+  const int pos0 = 4 * it;
+  int base = 0, sh = spread_log2;
+  while (sh > 0) {
+    const int full = ((nblk - base) >> (sh + 2)) << (sh + 2);   // entries in whole groups of 4e
+    if (pos0 - base < full) break;
+    base += full;
+    --sh;
+  }
+  const int rel = pos0 - base;
+  e_out = 1 << sh;
+  return base + ((rel >> (sh + 2)) << (sh + 2)) + ((rel & ((4 << sh) - 1)) >> 2);
 }
 
 // ---- end of a workgroup: from per-lane states to the output row ---------------
@@ -391,13 +420,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // loads inside the loop, where it otherwise falls back to a vector load and a
   // full wait.)  Indices past the range are clamped to its last entry.
   const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb + (SLICED ? 0 : wave));
-  struct Ids { int v[NID]; };
+  struct Ids { int v[NID]; int first, dist; };   // ids; sliced: entry of instruction 0 and distance to the next
   auto block_ids = [&](int it) {
     Ids r;
     if constexpr (SLICED) {
+      r.first = step_first_entry(min(it, n_it - 1), nblk, a.spread_log2, r.dist);
 #pragma unroll
-      for (int i = 0; i < NID; ++i) r.v[i] = tab[min(4 * it + i, nblk - 1)];
+      for (int i = 0; i < NID; ++i) r.v[i] = tab[min(r.first + i * r.dist, nblk - 1)];
     } else {
+      r.first = r.dist = 0;
       r.v[0] = tab[4 * min(it, n_it - 1)];
     }
     return r;
@@ -425,7 +456,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   auto load_tile = [&](int it, const char* base, const Ids& ids, v4u* td) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const bool real = SLICED ? 4 * it + i < nblk : it < n_it;
+      const bool real = it < n_it && (!SLICED || ids.first + i * ids.dist < nblk);
       const char* p = real ? base + (int64_t)ids.v[SLICED ? i : 0] * a.stride_block + lane_off + (SLICED ? 0u : i * inst_off)
                            : dummy;
       td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
@@ -436,7 +467,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   // context.
   auto token_limit = [&](int it, int i) {
     if constexpr (SLICED) {
-      const int bi = 4 * it + i;
+      int dist;
+      const int bi = step_first_entry(it, nblk, a.spread_log2, dist) + i * dist;
       return bi < nblk ? min(B, k - (jb + bi) * B) - 4 * wave : 0;
     } else {
       return k - (jb + wave + 4 * it) * B - i * TPI;
@@ -861,11 +893,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WMAX <= 3 ?
   const int n_it = (nblk + 3) / 4;
   v4u kcs[P][4], vcs[P][4];
   const ConstTable tab = (ConstTable)(a.bt + rq.bt + jb);
-  struct Ids { int v[4]; };
+  struct Ids { int v[4]; int first, dist; };   // ids, entry of instruction 0, distance to the next (step_first_entry)
   auto block_ids = [&](int it) {
     Ids r;
+    r.first = step_first_entry(min(it, n_it - 1), nblk, a.spread_log2, r.dist);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = tab[min(4 * it + i, nblk - 1)];
+    for (int i = 0; i < 4; ++i) r.v[i] = tab[min(r.first + i * r.dist, nblk - 1)];
     return r;
   };
   // tile of step `it`: instruction i reads the wave's rows of block 4*it + i, or the
@@ -873,7 +906,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WMAX <= 3 ?
   auto load_tile = [&](int it, const char* base, uint32_t off, const Ids& ids, v4u* td) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const char* p = 4 * it + i < nblk ? base + (int64_t)ids.v[i] * a.stride_block + off : dummy;
+      const char* p = it < n_it && ids.first + i * ids.dist < nblk ? base + (int64_t)ids.v[i] * a.stride_block + off : dummy;
       td[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
     }
   };
@@ -888,9 +921,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WMAX <= 3 ?
     v4u(&vc)[4] = vcs[S];
     // context rows of block 4*it + i, counted from this wave's first row
     int lim[4];
+    int e_dist = 1;
+    const int e_first = MASKED ? step_first_entry(it, nblk, a.spread_log2, e_dist) : 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int bi = 4 * it + i;
+      const int bi = e_first + i * e_dist;
       lim[i] = !MASKED ? 4 : (bi < nblk ? min(B, k - (jb + bi) * B) - 4 * wave : 0);
     }
     float s[4];
@@ -1299,6 +1334,14 @@ static int decode_impl(const kvm_pool* pool, const kvm_batch* reqs, const int32_
   a.H = l.n_kv_heads;
   a.Hq = l.n_q_heads;
   a.passes = p.passes;
+  {
+    // the four blocks of a step about 1 MiB apart when block ids are consecutive
+    // (step_first_entry); option "decode.spread" overrides (log2 of the entry distance)
+    int lg = 0;
+    while (lg < 6 && (a.stride_block << (lg + 1)) <= (1 << 20)) ++lg;
+    if (a.stride_block <= 0 || a.stride_block > (1 << 20)) lg = 0;
+    a.spread_log2 = options().decode_spread >= 0 ? options().decode_spread : lg;
+  }
   a.n_splits = p.n_splits;
   a.out_f32 = out_is_f32 ? 1 : 0;
   const float sc = scale == 0.f ? 1.0f / std::sqrt((float)l.head_dim) : scale;

@@ -353,6 +353,9 @@ int kvm_set_option(const char* name, int64_t value) {
   } else if (!strcmp(name, "decode.mfma")) {
     if (value < -1 || value > 1) return fail(KVM_EINVAL, "decode.mfma must be -1, 0 or 1");
     o.decode_mfma = (int)value;
+  } else if (!strcmp(name, "decode.spread")) {
+    if (value < -1 || value > 6) return fail(KVM_EINVAL, "decode.spread must be in [-1,6]");
+    o.decode_spread = (int)value;
   } else if (!strcmp(name, "decode.split_target")) {
     if (value < 1 || value > (1 << 20)) return fail(KVM_EINVAL, "decode.split_target must be in [1, 2^20]");
     o.decode_split_target = (int)value;

@@ -59,7 +59,8 @@ struct Options {
   int copy_order = -1;        // -1: by layout (plane outermost for layer-major pools); 1: plane outermost; 0: planes of a block consecutive
   int stage_linear = -1;      // -1: automatic (pack of long requests only); else bit 0: pack, bit 1: unpack cut along the staging buffer
   int decode_cap_waves = -1;    // -1: by group width and mean context length; 0 / 1: never / always cap at two waves per SIMD
-  int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks): -1 by group and context length, 0 never, 1 groups of 4 and 8
+  int decode_mfma = -1;         // scores on the matrix cores (head_dim 128, 16-token blocks, groups of 4 and 8): -1 and 1 yes, 0 never
+  int decode_spread = -1;       // -1: about 1 MiB between the four blocks of a decode step in consecutive ids; else log2 of the entry distance (0..6)
   int decode_split_target = 2048;  // workgroups a decode launch should reach by splitting contexts
   int decode_max_splits = 16;
   int decode_force_splits = 0;  // > 0: use exactly this many context splits

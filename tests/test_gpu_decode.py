@@ -89,13 +89,41 @@ def test_every_context_length_up_to_nine_blocks(oracle, m, variant):
     ref = oracle_decode(oracle, side, q)
     try:
         set_variant(variant)
-        for cap in (0, 1):
+        for cap, spread in ((0, -1), (1, -1), (0, 0), (1, 1)):
             kvm.kvm_set_option("decode.cap_waves", cap)
+            kvm.kvm_set_option("decode.spread", spread)
             got = gpu_decode(side, q)
             err = np.abs(got - ref).reshape(len(lens), -1).max(axis=1)
-            assert err.max() < TOL, (cap, int(err.argmax()) + 1, err.max())
+            assert err.max() < TOL, (cap, spread, int(err.argmax()) + 1, err.max())
     finally:
         kvm.kvm_set_option("decode.cap_waves", -1)
+        kvm.kvm_set_option("decode.spread", -1)
+        set_variant("shipped")
+
+
+@pytest.mark.parametrize("variant", ["matrix_core_scores", "vector_unit_scores"])
+@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2]], ids=["mha128", "gqa4"])
+def test_interleaved_block_order_at_every_spread(oracle, m, variant):
+    """A step of the head_dim-128 kernels reads four table entries that lie 2^spread
+    entries apart (groups of 4 * 2^spread entries, the remainder with halved distances,
+    the last entries in table order).  Contexts of 10 to 150 blocks with every kind of
+    last block, every spread: each entry must be read exactly once, and the partly
+    filled block last."""
+    lens = [16 * n + r for n in range(10, 150, 9) for r in (0, 1, 15)] + [16 * 129 + 7, 16 * 64, 16 * 256]
+    n_blocks = sum(-(-k // 16) for k in lens)
+    src, _ = make_pair(m, n_blocks + 8, 8, lens, [0] * len(lens), seed=33, finite=True)
+    side = Side(m, n_blocks + 8, src.host, src.tables, lens)
+    q = wl.gen_q(33, m, len(lens))
+    ref = oracle_decode(oracle, side, q)
+    try:
+        set_variant(variant)
+        for spread in range(0, 7):
+            kvm.kvm_set_option("decode.spread", spread)
+            got = gpu_decode(side, q)
+            err = np.abs(got - ref).reshape(len(lens), -1).max(axis=1)
+            assert err.max() < TOL, (spread, lens[int(err.argmax())], err.max())
+    finally:
+        kvm.kvm_set_option("decode.spread", -1)
         set_variant("shipped")
 
 

@@ -76,7 +76,7 @@ def test_decode_matches_oracle(oracle, m, variant):
 
 
 @pytest.mark.parametrize("variant", ["matrix_core_scores", "vector_unit_scores"])
-@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2]], ids=["mha128", "gqa4"])
+@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2], SHAPES[4]], ids=["mha128", "gqa4", "gqa8"])
 def test_every_context_length_up_to_nine_blocks(oracle, m, variant):
     """The kernels for head_dim 128 give each wave four token rows of every block and
     walk four blocks per step: every number of blocks modulo four and every fill of the
@@ -102,7 +102,7 @@ def test_every_context_length_up_to_nine_blocks(oracle, m, variant):
 
 
 @pytest.mark.parametrize("variant", ["matrix_core_scores", "vector_unit_scores"])
-@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2]], ids=["mha128", "gqa4"])
+@pytest.mark.parametrize("m", [SHAPES[1], SHAPES[2], SHAPES[4]], ids=["mha128", "gqa4", "gqa8"])
 def test_interleaved_block_order_at_every_spread(oracle, m, variant):
     """A step of the head_dim-128 kernels reads four table entries that lie 2^spread
     entries apart (groups of 4 * 2^spread entries, the remainder with halved distances,

@@ -6,19 +6,21 @@
 // usable.  One query token per (request, layer, query head):
 //   out = softmax(scale * q K^T) V  over tokens [0,k) read through the block table.
 //
-// The operation streams K and V once and does 1 (MHA) to 4 (grouped-query,
-// group 4) flops per byte, so it is bound by HBM and written for coalesced
-// 16-byte loads rather than for the matrix cores:
+// The operation streams K and V once and does 1 (MHA) to 8 (grouped-query, group
+// of eight) flops per byte, so it is bound by HBM and written around coalesced
+// 16-byte loads:
 //  - one 256-lane workgroup per (request, layer, KV head[, context split]); the
 //    G query heads that share the KV head are served from the same loads;
-//  - each of the 4 waves takes every 4th block of the range; within a wave a
-//    token row of D*2 bytes is spread over D/8 adjacent lanes (16 bytes each), so
-//    one load instruction covers 1 KiB of consecutive cache bytes;
-//  - q.K partial sums are reduced across those D/8 lanes with DPP lane
-//    permutes; every (wave, lane row) keeps its own online-softmax state
-//    (running max, sum, fp32 accumulator), merged through LDS at the end;
-//  - block ids are fetched 64 at a time, one per lane, and broadcast to the wave
-//    with readlane as the loop advances;
+//  - a token row of D*2 bytes is spread over D/8 adjacent lanes (16 bytes each), so
+//    one load instruction covers 1 KiB of consecutive cache bytes; for head_dim 128
+//    each of the 4 waves takes four token rows of EVERY block (other shapes: whole
+//    blocks, every 4th one per wave);
+//  - scores: dot instructions and DPP reductions on the vector unit, or, for groups
+//    of four and eight query heads, the matrix cores; P.V on the vector unit;
+//  - every (wave, lane row) keeps its own online-softmax state (running max, sum,
+//    fp32 accumulator); rows are merged in registers, waves through LDS by the wave
+//    that finishes last;
+//  - block ids come through scalar loads, one step ahead of their use;
 //  - long contexts can be split over several workgroups whose partial states are
 //    merged by a second small kernel (log-sum-exp merge).
 // The order of every reduction depends on logical token positions only, so the
@@ -340,11 +342,12 @@ __device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq&
   finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, ws, head_of);
 }
 
-// WMAX caps the waves per SIMD.  With long contexts the rate falls as more
-// workgroups stream concurrently (measured on MI355X, group 4, 7680 tokens: 6.4
-// TB/s at two waves per SIMD, 6.1 at three or four; MHA 6.65 at two, 6.4 at four),
-// with short ones (mean 550 tokens) the cap costs 11 % because set-up and merge
-// of a workgroup are no longer hidden; the host picks 2 or 8 by mean context.
+// WMAX caps the waves per SIMD.  The capped instance (two waves per SIMD, up to 256
+// registers each) keeps two tiles in flight per wave and is the faster one from about
+// a dozen blocks per workgroup on (measured on MI355X, one head per KV head, 32 blocks:
+// 6.64 against 6.37 TB/s); below that the uncapped instance wins because set-up and
+// merge of a workgroup are no longer hidden (8 blocks: 6.28 against 5.66).  The host
+// picks by mean context.
 template <int D, int B, int G, bool BF16, int WMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) void decode_kernel(const DecArgs a) {
   constexpr int LPT = D / 8;       // lanes per token row
@@ -582,8 +585,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WMAX))) 
   finish_workgroup<D, G, BF16>(a, rq, l, hq0, split, wave, lane, m, lsum, o, s_ws);
 }
 
-// Grouped-query decode with the scores on the matrix cores (groups of four or
-// eight query heads, head_dim 128, 16-token blocks).  q.K^T of one block is a
+// Grouped-query decode with the scores on the matrix cores, whole blocks per wave
+// (head_dim 128, 16-token blocks; launched for groups of eight query heads, groups
+// of four have decode_mfma4_kernel below).  q.K^T of one block is a
 // 16 x G x 128 contraction: four v_mfma_f32_16x16x32 with K as the A operand and
 // the query heads as columns of the B operand replace 64 dot instructions and 64
 // cross-lane additions of the vector version.

@@ -489,34 +489,66 @@ def main():
     reference = None
     if not a.no_reference_legs:
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
-        legs = [  # name, mode, run bytes, source random, destination random
-            ("read_stream", wl_device.REF_READ, 4096, False, False),
-            ("write_stream", wl_device.REF_WRITE, 4096, False, False),
-            ("read_random_4k", wl_device.REF_READ, 4096, True, False),
-            ("read_random_32k", wl_device.REF_READ, 32768, True, False),
-            ("write_random_32k", wl_device.REF_WRITE, 32768, False, True),
-            ("copy_stream", wl_device.REF_COPY, 32768, False, False),
-            ("copy_random_src_32k", wl_device.REF_COPY, 32768, True, False),
-            ("copy_random_dst_32k", wl_device.REF_COPY, 32768, False, True),
-            ("copy_random_both_32k", wl_device.REF_COPY, 32768, True, True),
+        legs = [  # name, mode, run bytes, source random, destination random, source / destination die rotation
+            ("read_stream", wl_device.REF_READ, 4096, False, False, 0, 0),
+            ("write_stream", wl_device.REF_WRITE, 4096, False, False, 0, 0),
+            ("read_random_4k", wl_device.REF_READ, 4096, True, False, 0, 0),
+            ("read_random_32k", wl_device.REF_READ, 32768, True, False, 0, 0),
+            ("write_random_32k", wl_device.REF_WRITE, 32768, False, True, 0, 0),
+            ("copy_stream", wl_device.REF_COPY, 32768, False, False, 0, 0),
+            ("copy_random_src_32k", wl_device.REF_COPY, 32768, True, False, 0, 0),
+            ("copy_random_dst_32k", wl_device.REF_COPY, 32768, False, True, 0, 0),
+            ("copy_random_both_32k", wl_device.REF_COPY, 32768, True, True, 0, 0),
+            # which 4 KiB pieces a die touches: workgroup c of a 32 KiB run takes chunk c
+            # (every die one residue class of pieces), chunk c + 1 (another fixed class) or
+            # chunk c + r in run r (a class that changes from run to run)
+            ("read_stream_32k", wl_device.REF_READ, 32768, False, False, 0, 0),
+            ("read_stream_32k_shifted", wl_device.REF_READ, 32768, False, False, 1, 0),
+            ("read_stream_32k_varying", wl_device.REF_READ, 32768, False, False, 8, 0),
+            ("write_stream_32k", wl_device.REF_WRITE, 32768, False, False, 0, 0),
+            ("write_stream_32k_shifted", wl_device.REF_WRITE, 32768, False, False, 0, 1),
+            ("write_stream_32k_varying", wl_device.REF_WRITE, 32768, False, False, 0, 8),
+            ("copy_stream_src_varying", wl_device.REF_COPY, 32768, False, False, 8, 0),
+            ("copy_stream_dst_varying", wl_device.REF_COPY, 32768, False, False, 0, 8),
+            ("copy_stream_both_varying", wl_device.REF_COPY, 32768, False, False, 8, 8),
         ]
         reference = {}
         ref_bytes = min(payload, 8 << 30)      # enough for a steady rate; fits every pool's permuted slots
-        for name, mode, run, rs, rd in legs:
-            n_runs = ref_bytes // run
-            args = (mode, src_mem if mode != wl_device.REF_WRITE else None,
-                    dst_mem if mode != wl_device.REF_READ else None, run, n_runs, rs, rd, sink)
+
+        def time_leg(name, fn, moved):
             for _ in range(2):
-                wl_device.ref_stream(*args)
+                fn()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(5):
-                wl_device.ref_stream(*args)
+                fn()
             e1.record(stream)
             torch.cuda.synchronize()
-            moved = n_runs * run * (2 if mode == wl_device.REF_COPY else 1)
             reference[name] = {"GB/s": round(moved * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1),
                                "bytes": moved}
+
+        for name, mode, run, rs, rd, srot, drot in legs:
+            n_runs = ref_bytes // run
+            args = (mode, src_mem if mode != wl_device.REF_WRITE else None,
+                    dst_mem if mode != wl_device.REF_READ else None, run, n_runs, rs, rd, sink, srot, drot)
+            time_leg(name, lambda: wl_device.ref_stream(*args),
+                     n_runs * run * (2 if mode == wl_device.REF_COPY else 1))
+        # the decode's read shape without its arithmetic: four waves walking sequences of
+        # 4 KiB pieces, four K-like and four V-like pieces per step (sixteen steps, as a
+        # context of 64 blocks), over the first 8 GiB of the source pool
+        walk_mem = src_mem[:min(src_mem.numel(), 8 << 30)]
+        walks = [  # name, pieces between the four pieces of a step, sliced
+            ("walk_piece_per_wave_1m_apart", 256, False),
+            ("walk_sliced_1m_apart", 256, True),
+            ("walk_sliced_adjacent", 1, True),
+            ("walk_sliced_32k_apart", 8, True),
+            ("walk_sliced_128k_apart", 32, True),
+            ("walk_sliced_512k_apart", 128, True),
+            ("walk_sliced_4m_apart", 1024, True),
+        ]
+        for name, stride, sliced in walks:
+            nbytes = wl_device.ref_walk(walk_mem, ref_bytes, stride, 16, sliced, sink)
+            time_leg(name, lambda: wl_device.ref_walk(walk_mem, ref_bytes, stride, 16, sliced, sink), nbytes)
         log("reference legs (GB/s): %s" % {k: v["GB/s"] for k, v in reference.items()})
 
     value = 6 * payload / (ms_step * 1e-3) / 1e9

@@ -38,8 +38,11 @@ def _load():
                                            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         _lib.kvmw_ref_stream.restype = ctypes.c_int
         _lib.kvmw_ref_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
-                                         ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
-                                         ctypes.c_void_p]
+                                         ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p]
+        _lib.kvmw_ref_walk.restype = ctypes.c_int
+        _lib.kvmw_ref_walk.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         _lib.kvmw_plain_copy.restype = ctypes.c_int
         _lib.kvmw_plain_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                          ctypes.c_void_p]
@@ -58,11 +61,12 @@ def plain_copy(dst, src, nbytes):
 REF_COPY, REF_READ, REF_WRITE = 0, 1, 2
 
 
-def ref_stream(mode, src, dst, run_bytes, n_runs, src_random, dst_random, sink):
+def ref_stream(mode, src, dst, run_bytes, n_runs, src_random, dst_random, sink, src_rot=0, dst_rot=0):
     """One launch of the reference access-pattern kernel (see fill.hip): n_runs runs of
     run_bytes each, read from `src` and / or written to `dst` (torch tensors spanning
     the buffers), at consecutive run slots or at pseudo-randomly permuted slots over
-    the largest power-of-two number of slots the buffer holds."""
+    the largest power-of-two number of slots the buffer holds.  *_rot: workgroup c of
+    run r takes 4 KiB chunk (c + (rot & 7) + (rot >> 3) * r) % chunks of that side."""
     import torch
 
     def bits(buf, random):
@@ -77,10 +81,25 @@ def ref_stream(mode, src, dst, run_bytes, n_runs, src_random, dst_random, sink):
     rc = _load().kvmw_ref_stream(mode, src.data_ptr() if src is not None else None,
                                  dst.data_ptr() if dst is not None else None, run_bytes, n_runs,
                                  bits(src, src_random) if src is not None else 0,
-                                 bits(dst, dst_random) if dst is not None else 0,
+                                 bits(dst, dst_random) if dst is not None else 0, int(src_rot), int(dst_rot),
                                  sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
     if rc != 0:
         raise RuntimeError("kvmw_ref_stream failed with %d" % rc)
+
+
+def ref_walk(src, n_bytes, stride_pieces, n_steps, sliced, sink):
+    """One launch of the walking read kernel (see fill.hip): workgroups of four waves that
+    each make n_steps steps of four 4 KiB pieces from the lower half of `src` and four from
+    the upper half; n_bytes in total (rounded down to whole workgroups).  Returns the bytes read."""
+    import torch
+    half_pieces = src.numel() * src.element_size() // 8192
+    n_wg = n_bytes // (n_steps * 8 * 4096)
+    assert n_wg >= 1 and 3 * stride_pieces < half_pieces
+    rc = _load().kvmw_ref_walk(src.data_ptr(), half_pieces, int(stride_pieces), int(n_steps), n_wg,
+                               1 if sliced else 0, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("kvmw_ref_walk failed with %d" % rc)
+    return n_wg * n_steps * 8 * 4096
 
 
 def fill_pool(mem, model, n_blocks, seed, stream_id, strides=None, b0=0, b1=None):

@@ -246,6 +246,7 @@ struct RefArgs {
   uint32_t run_vecs, chunks;     // vectors per run, workgroups per run
   uint64_t n_runs;
   uint32_t src_bits, dst_bits;
+  uint32_t src_rot, dst_rot;     // workgroup c of run r takes chunk (c + (rot & 7) + (rot >> 3) * r) % chunks on that side
   int32_t mode;
   uint32_t* sink;                // read-only mode: never written unless a loaded word equals the magic
 };
@@ -264,11 +265,16 @@ __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
   const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
   const uint64_t r = w / a.chunks;
   if (r >= a.n_runs) return;
-  const uint32_t v = (uint32_t)(w - r * a.chunks) * 256u + threadIdx.x;
+  const uint32_t c = (uint32_t)(w - r * a.chunks);
+  const uint32_t v = c * 256u + threadIdx.x;
   if (v >= a.run_vecs) return;
+  // rotated sides are only offered for runs of whole chunks (checked on the host)
+  const uint32_t rr = (uint32_t)(r % a.chunks);
+  const uint32_t sv = ((c + (a.src_rot & 7u) + (a.src_rot >> 3) * rr) % a.chunks) * 256u + threadIdx.x;
+  const uint32_t dv = ((c + (a.dst_rot & 7u) + (a.dst_rot >> 3) * rr) % a.chunks) * 256u + threadIdx.x;
   const uint64_t s_slot = ref_perm(r, a.src_bits), d_slot = ref_perm(r, a.dst_bits);
-  const kvmw_v4u* sp = reinterpret_cast<const kvmw_v4u*>(a.src) + s_slot * a.run_vecs + v;
-  kvmw_v4u* dp = reinterpret_cast<kvmw_v4u*>(a.dst) + d_slot * a.run_vecs + v;
+  const kvmw_v4u* sp = reinterpret_cast<const kvmw_v4u*>(a.src) + s_slot * a.run_vecs + sv;
+  kvmw_v4u* dp = reinterpret_cast<kvmw_v4u*>(a.dst) + d_slot * a.run_vecs + dv;
   kvmw_v4u x = {v, v, v, v};
   if (a.mode != 2)
     asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(x) : "v"(sp) : "memory");
@@ -281,12 +287,18 @@ __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
 // bytes = n_runs * run_bytes are moved.  *_bits = 0: runs at consecutive slots; else
 // permuted over the side's first 2^bits slots (the buffer must hold them, and
 // n_runs <= 2^bits).  Returns 0, -1 on a bad argument, or the hipError_t of the launch.
+// *_rot: workgroup c of run r works on chunk (c + (rot & 7) + (rot >> 3) * r) % chunks of
+// that side instead of chunk c.  Workgroups go to the eight dies round-robin, so with
+// eight chunks per run rot = 0 lets every die touch one residue class of 4 KiB pieces
+// (its own number), rot = 1..7 another fixed class, and rot = 8 a class that changes
+// from run to run.  Needs runs of whole 4 KiB chunks.
 extern "C" int kvmw_ref_stream(int mode, const void* src_dev, void* dst_dev, int64_t run_bytes,
-                               int64_t n_runs, int src_bits, int dst_bits, void* sink_dev,
-                               void* hip_stream) {
+                               int64_t n_runs, int src_bits, int dst_bits, int src_rot, int dst_rot,
+                               void* sink_dev, void* hip_stream) {
   if (mode < 0 || mode > 2 || run_bytes <= 0 || run_bytes % 16 || n_runs <= 0 || src_bits < 0 ||
-      src_bits > 40 || dst_bits < 0 || dst_bits > 40)
+      src_bits > 40 || dst_bits < 0 || dst_bits > 40 || src_rot < 0 || src_rot > 63 || dst_rot < 0 || dst_rot > 63)
     return -1;
+  if ((src_rot || dst_rot) && run_bytes % 4096) return -1;
   if ((src_bits && n_runs > (1ll << src_bits)) || (dst_bits && n_runs > (1ll << dst_bits))) return -1;
   if ((mode != 2 && !src_dev) || (mode != 1 && !dst_dev) || (mode == 1 && !sink_dev)) return -1;
   RefArgs a;
@@ -297,6 +309,8 @@ extern "C" int kvmw_ref_stream(int mode, const void* src_dev, void* dst_dev, int
   a.n_runs = (uint64_t)n_runs;
   a.src_bits = (uint32_t)src_bits;
   a.dst_bits = (uint32_t)dst_bits;
+  a.src_rot = (uint32_t)src_rot;
+  a.dst_rot = (uint32_t)dst_rot;
   a.mode = mode;
   a.sink = (uint32_t*)sink_dev;
   const uint64_t n_wg = a.n_runs * a.chunks;
@@ -304,5 +318,97 @@ extern "C" int kvmw_ref_stream(int mode, const void* src_dev, void* dst_dev, int
   const uint32_t gx = n_wg < 65536 ? (uint32_t)n_wg : 65536u;
   const uint32_t gy = (uint32_t)((n_wg + 65535) / 65536);
   hipLaunchKernelGGL(ref_stream_kernel, dim3(gx, gy), dim3(256), 0, (hipStream_t)hip_stream, a);
+  return (int)hipGetLastError();
+}
+
+// ---- reference: waves that walk sequences of 4 KiB pieces -----------------------
+// The read shape of a paged decode without its arithmetic: a workgroup of four waves
+// makes n_steps steps; a step reads four 4 KiB pieces of a K-like stream (the lower half
+// of the buffer) and the four pieces at the same offsets of a V-like stream (the upper
+// half), two steps in flight.  The four pieces of a step lie stride_pieces * 4 KiB apart,
+// the first at a pseudo-random place.
+//   sliced = 0: wave w reads piece w of the step whole (four loads of 1 KiB)
+//   sliced = 1: every wave reads quarter w of all four pieces (four loads of 1 KiB)
+// Same bytes, same addresses, same number of loads: only who reads what differs.
+struct WalkArgs {
+  const char* src;
+  uint64_t half_pieces;    // pieces per stream
+  uint32_t stride_pieces;
+  int32_t n_steps;
+  int32_t sliced;
+  uint64_t n_wg;
+  uint32_t* sink;
+};
+
+__device__ inline uint64_t walk_mix(uint64_t r) {
+  r *= 0x9E3779B97F4A7C15ull;
+  r ^= r >> 29;
+  r *= 0xBF58476D1CE4E5B9ull;
+  r ^= r >> 32;
+  return r;
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void ref_walk_kernel(const WalkArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint64_t wg = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+  if (wg >= a.n_wg) return;
+  const uint64_t span = a.half_pieces - 3ull * a.stride_pieces;   // first pieces that keep the step in bounds
+  kvmw_v4u t[2][2][4];
+  auto issue = [&](int step, int slot) {
+    const uint64_t base = walk_mix(wg * (uint64_t)a.n_steps + (uint64_t)step) % span;
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // sliced: piece j, quarter `wave`; else: piece `wave`, quarter j
+        const uint64_t piece = base + (uint64_t)(a.sliced ? j : wave) * a.stride_pieces;
+        const uint32_t quarter = a.sliced ? (uint32_t)wave : (uint32_t)j;
+        t[slot][s][j] = __builtin_nontemporal_load(reinterpret_cast<const kvmw_v4u*>(
+            a.src + ((uint64_t)s * a.half_pieces + piece) * 4096 + quarter * 1024u + (uint32_t)lane * 16u));
+      }
+  };
+  uint32_t x = 0;
+  auto consume = [&](int slot) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x ^= t[slot][s][j][0] ^ t[slot][s][j][1] ^ t[slot][s][j][2] ^ t[slot][s][j][3];
+  };
+  issue(0, 0);
+  issue(a.n_steps > 1 ? 1 : 0, 1);
+  for (int it = 0; it + 2 <= a.n_steps; it += 2) {   // past the end: the last step again
+    consume(0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(it + 2 < a.n_steps ? it + 2 : a.n_steps - 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(1);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(it + 3 < a.n_steps ? it + 3 : a.n_steps - 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  consume(0);
+  consume(1);
+  if (x == 0x5EEDF00Du && a.sink) *a.sink = x;   // keeps the loads observable; practically never taken
+}
+
+// Reads n_wg * n_steps * 8 pieces (32 KiB per workgroup and step) of a buffer of
+// 2 * half_pieces pieces.  Returns 0, -1 on a bad argument, or the hipError_t of the launch.
+extern "C" int kvmw_ref_walk(const void* src_dev, int64_t half_pieces, int stride_pieces, int n_steps,
+                             int64_t n_wg, int sliced, void* sink_dev, void* hip_stream) {
+  if (!src_dev || !sink_dev || half_pieces <= 0 || stride_pieces < 1 || n_steps < 1 || n_wg < 1 ||
+      n_wg > 0x7fffffffll || 3ll * stride_pieces >= half_pieces)
+    return -1;
+  WalkArgs a;
+  a.src = (const char*)src_dev;
+  a.half_pieces = (uint64_t)half_pieces;
+  a.stride_pieces = (uint32_t)stride_pieces;
+  a.n_steps = n_steps;
+  a.sliced = sliced ? 1 : 0;
+  a.n_wg = (uint64_t)n_wg;
+  a.sink = (uint32_t*)sink_dev;
+  const uint32_t gx = n_wg < 65536 ? (uint32_t)n_wg : 65536u;
+  const uint32_t gy = (uint32_t)((n_wg + 65535) / 65536);
+  hipLaunchKernelGGL(ref_walk_kernel, dim3(gx, gy), dim3(256), 0, (hipStream_t)hip_stream, a);
   return (int)hipGetLastError();
 }

@@ -54,3 +54,50 @@ def test_block_hash_matches_numpy_and_sees_moved_words():
     h2 = wl_device.plane_block_hashes(mem, m, n_blocks).cpu().numpy().view(np.uint64)
     diff = h2 != h
     assert diff[1, 5] and diff.sum() == 1
+
+
+def test_reference_copy_moves_the_chunks_it_says():
+    """The table-free reference kernel the benchmark times (runs at consecutive or permuted
+    slots, chunks of a run optionally shifted by some dies) is a copy: every chunk of the
+    source arrives exactly once, where the host's model of the kernel puts it."""
+    run, n_runs, slots = 32768, 48, 64
+    rng = np.random.default_rng(5)
+    src_h = rng.integers(0, 2**31, size=slots * run // 4, dtype=np.int32)
+    src = torch.from_numpy(src_h).to(DEV)
+    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+
+    def perm(r, bits):
+        if bits == 0:
+            return r
+        mask = (1 << bits) - 1
+        r = (r * 0x9E3779B97F4A7C15) & mask
+        r ^= r >> ((bits + 1) // 2)
+        r = (r * 0xBF58476D1CE4E5B9) & mask
+        r ^= r >> ((bits + 1) // 2)
+        return r
+
+    for s_rand, d_rand, s_rot, d_rot in ((False, False, 0, 0), (True, False, 1, 0), (False, True, 0, 3), (True, True, 5, 2),
+                                         (False, False, 8, 0), (True, True, 9, 8)):
+        dst = torch.full_like(src, -1)
+        wl_device.ref_stream(wl_device.REF_COPY, src, dst, run, n_runs, s_rand, d_rand, sink, s_rot, d_rot)
+        torch.cuda.synchronize()
+        exp = np.full_like(src_h, -1).reshape(slots, 8, 1024)
+        s3 = src_h.reshape(slots, 8, 1024)
+        for r in range(n_runs):
+            for c in range(8):
+                exp[perm(r, 6 if d_rand else 0), (c + (d_rot & 7) + (d_rot >> 3) * (r % 8)) % 8] = \
+                    s3[perm(r, 6 if s_rand else 0), (c + (s_rot & 7) + (s_rot >> 3) * (r % 8)) % 8]
+        assert np.array_equal(dst.cpu().numpy().reshape(slots, 8, 1024), exp), (s_rand, d_rand, s_rot, d_rot)
+
+
+def test_reference_walk_runs_in_bounds_sizes():
+    """The walking read kernel only reads: it must accept the sizes the benchmark uses and
+    refuse a stride that would leave the buffer."""
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device=DEV)           # 2 x 8192 pieces
+    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+    for stride, sliced in ((1, True), (256, True), (256, False), (2000, True)):
+        assert wl_device.ref_walk(buf, 16 << 20, stride, 16, sliced, sink) == 16 << 20
+    torch.cuda.synchronize()
+    with pytest.raises(AssertionError):
+        wl_device.ref_walk(buf, 16 << 20, 3000, 16, True, sink)                  # 3 * 3000 >= 8192 pieces
+    assert int(sink.sum()) == 0

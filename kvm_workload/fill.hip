@@ -269,9 +269,12 @@ __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
   const uint32_t v = c * 256u + threadIdx.x;
   if (v >= a.run_vecs) return;
   // rotated sides are only offered for runs of whole chunks (checked on the host)
-  const uint32_t rr = (uint32_t)(r % a.chunks);
-  const uint32_t sv = ((c + (a.src_rot & 7u) + (a.src_rot >> 3) * rr) % a.chunks) * 256u + threadIdx.x;
-  const uint32_t dv = ((c + (a.dst_rot & 7u) + (a.dst_rot >> 3) * rr) % a.chunks) * 256u + threadIdx.x;
+  uint32_t sv = v, dv = v;
+  if (a.src_rot | a.dst_rot) {   // uniform; chunks is a power of two here (checked on the host): masks, no division
+    const uint32_t mask = a.chunks - 1u, rr = (uint32_t)r;
+    sv = ((c + (a.src_rot & 7u) + (a.src_rot >> 3) * rr) & mask) * 256u + threadIdx.x;
+    dv = ((c + (a.dst_rot & 7u) + (a.dst_rot >> 3) * rr) & mask) * 256u + threadIdx.x;
+  }
   const uint64_t s_slot = ref_perm(r, a.src_bits), d_slot = ref_perm(r, a.dst_bits);
   const kvmw_v4u* sp = reinterpret_cast<const kvmw_v4u*>(a.src) + s_slot * a.run_vecs + sv;
   kvmw_v4u* dp = reinterpret_cast<kvmw_v4u*>(a.dst) + d_slot * a.run_vecs + dv;
@@ -291,14 +294,14 @@ __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
 // that side instead of chunk c.  Workgroups go to the eight dies round-robin, so with
 // eight chunks per run rot = 0 lets every die touch one residue class of 4 KiB pieces
 // (its own number), rot = 1..7 another fixed class, and rot = 8 a class that changes
-// from run to run.  Needs runs of whole 4 KiB chunks.
+// from run to run.  Needs runs of a power-of-two number of whole 4 KiB chunks.
 extern "C" int kvmw_ref_stream(int mode, const void* src_dev, void* dst_dev, int64_t run_bytes,
                                int64_t n_runs, int src_bits, int dst_bits, int src_rot, int dst_rot,
                                void* sink_dev, void* hip_stream) {
   if (mode < 0 || mode > 2 || run_bytes <= 0 || run_bytes % 16 || n_runs <= 0 || src_bits < 0 ||
       src_bits > 40 || dst_bits < 0 || dst_bits > 40 || src_rot < 0 || src_rot > 63 || dst_rot < 0 || dst_rot > 63)
     return -1;
-  if ((src_rot || dst_rot) && run_bytes % 4096) return -1;
+  if ((src_rot || dst_rot) && (run_bytes % 4096 || ((run_bytes / 4096) & (run_bytes / 4096 - 1)))) return -1;
   if ((src_bits && n_runs > (1ll << src_bits)) || (dst_bits && n_runs > (1ll << dst_bits))) return -1;
   if ((mode != 2 && !src_dev) || (mode != 1 && !dst_dev) || (mode == 1 && !sink_dev)) return -1;
   RefArgs a;

@@ -198,11 +198,14 @@ def test_options_and_strerror():
     L = kvm.lib()
     assert L.kvm_strerror(0) == b"ok" and L.kvm_strerror(-2) == b"free list exhausted"
     for name, val in (("copy.order", 2), ("copy.nontemporal", 2), ("nope", 1), ("copy.unroll", 1),
-                      ("decode.max_splits", 0), ("decode.force_splits", 65)):
+                      ("decode.max_splits", 0), ("decode.force_splits", 65), ("decode.spread", 7),
+                      ("decode.spread", -2)):
         with pytest.raises(kvm.KvmError):
             kvm.kvm_set_option(name, val)
     kvm.kvm_set_option("copy.order", -1)
     kvm.kvm_set_option("decode.force_splits", 0)
+    kvm.kvm_set_option("decode.spread", 6)
+    kvm.kvm_set_option("decode.spread", -1)
 
 
 def test_per_request_limit_is_checked_before_the_first_launch():

@@ -238,8 +238,7 @@ extern "C" int kvmw_plain_copy(void* dst_dev, const void* src_dev, int64_t bytes
 // The buffer on each side is cut into runs of `run_vecs` vectors; workgroup w works
 // on chunk (w % chunks) of run (w / chunks); run r sits at run slot r of its side
 // (bits = 0: sequential) or at slot perm(r), a fixed pseudo-random permutation of
-// the side's first 2^bits slots (multiply by an odd constant, xor the upper half
-// into the lower, multiply again: each step is a bijection on `bits`-bit values).
+// the side's first 2^bits slots (ref_perm below).
 struct RefArgs {
   const char* src;
   char* dst;
@@ -251,15 +250,25 @@ struct RefArgs {
   uint32_t* sink;                // read-only mode: never written unless a loaded word equals the magic
 };
 
-__device__ inline uint64_t ref_perm(uint64_t r, uint32_t bits) {
+// A bijection on `bits`-bit values: add a key, then multiply by odd constants, fold the
+// upper half into the lower and rotate by half the width (a product's low bits depend
+// on low bits only; the rotation hands them to the next product's upper bits).  The two
+// sides of a copy use different keys, so their run slots are unrelated.
+__device__ inline uint64_t ref_perm(uint64_t r, uint32_t bits, uint64_t key) {
   if (bits == 0) return r;
   const uint64_t mask = (1ull << bits) - 1;
+  const uint32_t h = (bits + 1) / 2;
+  r = (r + key) & mask;
   r = (r * 0x9E3779B97F4A7C15ull) & mask;
-  r ^= r >> ((bits + 1) / 2);
+  r ^= r >> h;
+  r = ((r << h) | (r >> (bits - h))) & mask;
   r = (r * 0xBF58476D1CE4E5B9ull) & mask;
-  r ^= r >> ((bits + 1) / 2);
+  r ^= r >> h;
+  r = (r * 0x94D049BB133111EBull) & mask;
+  r ^= r >> h;
   return r;
 }
+constexpr uint64_t kRefKeySrc = 0, kRefKeyDst = 0x5851F42D4C957F2Dull;
 
 __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
   const uint64_t w = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
@@ -275,7 +284,7 @@ __global__ __launch_bounds__(256) void ref_stream_kernel(const RefArgs a) {
     sv = ((c + (a.src_rot & 7u) + (a.src_rot >> 3) * rr) & mask) * 256u + threadIdx.x;
     dv = ((c + (a.dst_rot & 7u) + (a.dst_rot >> 3) * rr) & mask) * 256u + threadIdx.x;
   }
-  const uint64_t s_slot = ref_perm(r, a.src_bits), d_slot = ref_perm(r, a.dst_bits);
+  const uint64_t s_slot = ref_perm(r, a.src_bits, kRefKeySrc), d_slot = ref_perm(r, a.dst_bits, kRefKeyDst);
   const kvmw_v4u* sp = reinterpret_cast<const kvmw_v4u*>(a.src) + s_slot * a.run_vecs + sv;
   kvmw_v4u* dp = reinterpret_cast<kvmw_v4u*>(a.dst) + d_slot * a.run_vecs + dv;
   kvmw_v4u x = {v, v, v, v};

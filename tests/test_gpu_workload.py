@@ -66,16 +66,21 @@ def test_reference_copy_moves_the_chunks_it_says():
     src = torch.from_numpy(src_h).to(DEV)
     sink = torch.zeros(4, dtype=torch.int32, device=DEV)
 
-    def perm(r, bits):
+    def perm(r, bits, key):
         if bits == 0:
             return r
-        mask = (1 << bits) - 1
+        mask, h = (1 << bits) - 1, (bits + 1) // 2
+        r = (r + key) & mask
         r = (r * 0x9E3779B97F4A7C15) & mask
-        r ^= r >> ((bits + 1) // 2)
+        r ^= r >> h
+        r = ((r << h) | (r >> (bits - h))) & mask
         r = (r * 0xBF58476D1CE4E5B9) & mask
-        r ^= r >> ((bits + 1) // 2)
+        r ^= r >> h
+        r = (r * 0x94D049BB133111EB) & mask
+        r ^= r >> h
         return r
 
+    key_s, key_d = 0, 0x5851F42D4C957F2D
     for s_rand, d_rand, s_rot, d_rot in ((False, False, 0, 0), (True, False, 1, 0), (False, True, 0, 3), (True, True, 5, 2),
                                          (False, False, 8, 0), (True, True, 9, 8)):
         dst = torch.full_like(src, -1)
@@ -85,8 +90,8 @@ def test_reference_copy_moves_the_chunks_it_says():
         s3 = src_h.reshape(slots, 8, 1024)
         for r in range(n_runs):
             for c in range(8):
-                exp[perm(r, 6 if d_rand else 0), (c + (d_rot & 7) + (d_rot >> 3) * (r % 8)) % 8] = \
-                    s3[perm(r, 6 if s_rand else 0), (c + (s_rot & 7) + (s_rot >> 3) * (r % 8)) % 8]
+                exp[perm(r, 6 if d_rand else 0, key_d), (c + (d_rot & 7) + (d_rot >> 3) * (r % 8)) % 8] = \
+                    s3[perm(r, 6 if s_rand else 0, key_s), (c + (s_rot & 7) + (s_rot >> 3) * (r % 8)) % 8]
         assert np.array_equal(dst.cpu().numpy().reshape(slots, 8, 1024), exp), (s_rand, d_rand, s_rot, d_rot)
 
 

@@ -53,7 +53,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="llama3_8b_gqa")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="requests in the oracle's sample")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="requests in the oracle's sample")
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--order", type=int, default=None)
     ap.add_argument("--split-target", type=int, default=None)

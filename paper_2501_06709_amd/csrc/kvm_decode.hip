@@ -310,16 +310,34 @@ __device__ __forceinline__ void finish_workgroup(const DecArgs& a, const DecReq&
     const int hq = hq0 + g;
     if (a.n_splits == 1) {
       const int64_t oi = (((int64_t)rq.row * a.L + l) * a.Hq + hq) * D + d0;
-      // (out is only required to be 4-byte aligned: dword stores)
+      // out is only required to be 4-byte aligned; a 16-byte aligned one (a row starts
+      // at a multiple of 16 bytes from it) gets 16-byte stores: a quarter of the write
+      // requests the workgroup has to see acknowledged before it can end
+      const bool wide = (reinterpret_cast<uintptr_t>(a.out) & 15u) == 0;
+      float r[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) r[c] = acc[c] / den;
       if (a.out_f32) {
         float* dst = reinterpret_cast<float*>(a.out) + oi;
+        if (wide) {
+          reinterpret_cast<v4f*>(dst)[0] = v4f{r[0], r[1], r[2], r[3]};
+          reinterpret_cast<v4f*>(dst)[1] = v4f{r[4], r[5], r[6], r[7]};
+        } else {
 #pragma unroll
-        for (int c = 0; c < 8; ++c) dst[c] = acc[c] / den;
+          for (int c = 0; c < 8; ++c) dst[c] = r[c];
+        }
       } else {
         uint32_t* dst = reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(a.out) + oi);
+        uint32_t pk[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          dst[c] = (uint32_t)narrow<BF16>(acc[2 * c] / den) | ((uint32_t)narrow<BF16>(acc[2 * c + 1] / den) << 16);
+          pk[c] = (uint32_t)narrow<BF16>(r[2 * c]) | ((uint32_t)narrow<BF16>(r[2 * c + 1]) << 16);
+        if (wide) {
+          *reinterpret_cast<v4u*>(dst) = v4u{pk[0], pk[1], pk[2], pk[3]};
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) dst[c] = pk[c];
+        }
       }
     } else {
       float* e = ws_entry(a.ws, a, rq.slot, l, hq, split, D);

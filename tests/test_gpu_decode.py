@@ -199,6 +199,32 @@ def test_sixteen_bit_output(oracle):
         assert (np.abs(got - ref) <= ulp).all(), (np.abs(got - ref) / ulp).max()
 
 
+def test_output_at_four_byte_alignment_gives_the_same_bits():
+    """The output may start at any multiple of 4 bytes; the kernels then store dwords
+    instead of 16-byte pieces.  Same bits, and nothing outside the rows is written."""
+    for m in (wl.Model("h", 2, 2, 2, 128, 16, "f16"), wl.Model("b", 2, 2, 8, 128, 16, "bf16"),
+              wl.Model("e", 1, 1, 8, 128, 16, "f16"), wl.Model("t", 2, 4, 4, 64, 16, "f16")):
+        lens = [90, 5, 33]
+        src, _ = make_pair(m, 16, 8, lens, [0, 0, 0], seed=27, finite=True)
+        side = Side(m, 16, src.host, src.tables, lens)
+        q = wl.gen_q(27, m, 3)
+        q_dev = to_dev(q)
+        n = int(np.prod(q.shape))
+        for f32 in (True, False):
+            dt = torch.float32 if f32 else torch.int16
+            step = 1 if f32 else 2          # elements in 4 bytes
+            ref = torch.zeros(n, dtype=dt, device=DEV)
+            kvm.kvm_paged_decode(side.pool, side.batch, q_dev, ref, out_is_f32=f32)
+            for shift in (1, 2, 3):
+                buf = torch.full((n + 8 * step,), 5, dtype=dt, device=DEV)
+                out = buf[shift * step: shift * step + n]
+                assert out.data_ptr() % 16 == 4 * shift
+                kvm.kvm_paged_decode(side.pool, side.batch, q_dev, out, out_is_f32=f32)
+                torch.cuda.synchronize()
+                assert torch.equal(out, ref), (m.name, f32, shift)
+                assert (buf[:shift * step] == 5).all() and (buf[shift * step + n:] == 5).all()
+
+
 def test_garbage_beyond_the_context_is_ignored(oracle):
     """Slots >= k of the last block and blocks past it may hold NaN patterns."""
     m = wl.Model("nan", 1, 2, 4, 128, 16, "bf16")
